@@ -1,0 +1,259 @@
+#!/usr/bin/env python3
+"""Benchmark of the OQM hot path on one MI355X.
+
+One step = one pass of the whole path over one batch of synthetic input:
+    quantize-append of `frames_per_append` frames (all layers, K and V)
+    -> score all stored frame-groups against a T_q-token query
+    -> top-k per layer -> dequant-gather of the k groups into the bf16 active KV buffer.
+All inputs are resident in HBM before the timed region.  The store is pre-filled, and every
+step overwrites a rotating window of group slots so that it always holds the full stream.
+
+Prints ONE JSON line (see README / DESIGN notes for the field meanings).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
+METRIC = "OQM quantize-append + retrieve/dequant HBM GB/s (% of peak); retrieval ms/query"
+
+
+def bytes_append(w, n_frames, in_bytes):
+    e = n_frames * w.n_layers * 2 * w.n_kv_heads * w.group_tokens * w.head_dim
+    keys = n_frames * w.n_layers * w.n_kv_heads * w.head_dim * 4
+    return e * in_bytes + e // 2 + (e // w.qgroup) * 8 + keys, e
+
+
+def bytes_gather(w, k_eff, out_bytes):
+    e = w.n_layers * k_eff * 2 * w.n_kv_heads * w.group_tokens * w.head_dim
+    return e // 2 + (e // w.qgroup) * 8 + e * out_bytes + w.n_layers * k_eff * 4, e
+
+
+def bytes_score(w, T, q_bytes):
+    hd = w.n_kv_heads * w.head_dim
+    return w.n_layers * T * hd * 4 + w.n_layers * w.n_q_heads * w.t_q * w.head_dim * q_bytes + w.n_layers * T * 4
+
+
+def bytes_topk(w, T, k_eff):
+    return w.n_layers * T * 4 + w.n_layers * k_eff * 4
+
+
+def cpu_baseline(w, batches_cpu, q_cpu, threads):
+    """The oracle, as it stands, on a bounded sample of the same workload: the given append
+    batches (all layers) and one retrieval over what they stored.  Threads split layers."""
+    from concurrent.futures import ThreadPoolExecutor
+
+    import numpy as np
+
+    import synth_kv
+    from oracle import oqm_oracle as orc
+
+    dt = {"f32": 0, "bf16": 1, "f16": 2}[w.dtype]
+    F = sum(b[0].shape[0] for b in batches_cpu)
+    cfg = orc.make_config(w.n_layers, w.n_kv_heads, w.n_q_heads, w.head_dim, w.group_tokens,
+                          w.qgroup, F, in_dtype=dt, out_dtype=dt, sim=1 if w.sim == "cosine" else 0)
+    st = orc.new_store(cfg)
+    L = w.n_layers
+    threads = max(1, min(threads, L))
+    kb = [(synth_kv.as_numpy_bits(k), synth_kv.as_numpy_bits(v)) for k, v in batches_cpu]
+    qb = synth_kv.as_numpy_bits(q_cpu)
+    H, G, d = w.n_kv_heads, w.group_tokens, w.head_dim
+    strides = (L * H * G * d, H * G * d, G * d, d)
+    k_eff = min(w.top_k, F)
+    scores = np.zeros((L, F), np.float32)
+    idx = np.zeros((L, w.top_k), np.int32)
+    kout = np.zeros((L, H, w.top_k * G, d), np.uint16 if dt else np.float32)
+    vout = np.zeros_like(kout)
+
+    def layer_job(l):
+        first = 0
+        for k, v in kb:
+            nf = k.shape[0]
+            st_l = orc.Store(st.cfg, st.codes, st.scale, st.zero, st.keys, first)
+            orc.quantize_append(st_l, k.ravel()[l * strides[1]:], v.ravel()[l * strides[1]:], None,
+                                layer0=l, strides=strides, n_frames=nf, n_layers=1)
+            first += nf
+        st_l = orc.Store(st.cfg, st.codes, st.scale, st.zero, st.keys, F)
+        s = orc.score_groups(st_l, qb[l:l + 1], dt, layer0=l, n_layers=1)
+        scores[l] = s[0]
+        ii, _ = orc.topk(s, w.top_k)
+        idx[l] = ii[0]
+        ko, vo = orc.dequant_gather(st_l, ii, k_eff, layer0=l)
+        kout[l], vout[l] = ko[0], vo[0]
+
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        list(ex.map(layer_job, range(L)))
+    dtm = time.perf_counter() - t0
+    eb = 4 if w.dtype == "f32" else 2
+    ba, ea = bytes_append(w, F, eb)
+    bg, eg = bytes_gather(w, k_eff, eb)
+    total = ba + bg + bytes_score(w, F, eb) + bytes_topk(w, F, k_eff)
+    return {"value": total / dtm / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
+            "sample": f"{F} frames x {L} layers appended ({len(kb)} calls) + 1 query "
+                      f"(T_q={w.t_q}) scored over {F} groups, top-{k_eff} dequant-gathered; "
+                      f"{ea + eg} K/V elements in {dtm:.2f} s",
+            "tokens_per_s_append": None, "seconds": dtm}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="C3", choices=["C2", "C3", "C4", "C5"])
+    ap.add_argument("--frames-per-append", type=int, default=0, help="override the workload's batch")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-batches", type=int, default=4)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the path has no collectives); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import synth_kv
+    from paper_2510_18269_amd import oqm          # raises if the HIP library is missing
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = "cuda:0"
+    w = synth_kv.WORKLOADS[args.workload]
+    fpa = args.frames_per_append or (w.frames_per_append if w.frames_per_append > 1 else 1)
+    fpa = min(fpa, w.n_frames)
+    T = (w.n_frames // fpa) * fpa
+    eb = 4 if w.dtype == "f32" else 2
+    dtc = {"f32": oqm.TOM_F32, "bf16": oqm.TOM_BF16, "f16": oqm.TOM_F16}[w.dtype]
+    cfg = oqm.make_config(w.n_layers, w.n_kv_heads, w.n_q_heads, w.head_dim, w.group_tokens,
+                          w.qgroup, T, in_dtype=dtc, out_dtype=dtc,
+                          sim=oqm.TOM_SIM_COSINE if w.sim == "cosine" else oqm.TOM_SIM_DOT)
+    mem = oqm.Memory.allocate(cfg, dev)
+    L = w.n_layers
+
+    # distinct input batches, more than the 256 MB last-level cache can hold, rotated per step
+    batch_bytes = bytes_append(w, fpa, eb)[0]
+    n_batches = max(2, min(T // fpa, int(3.0e9 // max(batch_bytes, 1)) or 1, 64))
+    batches = [synth_kv.kv_frames(w, i * fpa, fpa, dev) for i in range(n_batches)]
+    queries = [synth_kv.query(w, i, dev) for i in range(4)]
+    path = oqm.TOM_SCORE_TOKEN_GEMM if args.workload == "C5" else oqm.TOM_SCORE_MEAN_QUERY
+    ws = torch.empty(oqm.tom_oqm_score_workspace_bytes(mem.handle, L, w.t_q, path), dtype=torch.uint8,
+                     device=dev)
+    scores = torch.zeros((L, T), dtype=torch.float32, device=dev)
+    idx = torch.zeros((L, w.top_k), dtype=torch.int32, device=dev)
+    tdt = synth_kv.torch_dtype(w)
+    outs = [(torch.empty((L, w.n_kv_heads, w.top_k * w.group_tokens, w.head_dim), dtype=tdt, device=dev),
+             torch.empty((L, w.n_kv_heads, w.top_k * w.group_tokens, w.head_dim), dtype=tdt, device=dev))
+            for _ in range(2)]
+    k_eff = min(w.top_k, T)
+
+    # pre-fill the whole store (untimed)
+    for i in range(T // fpa):
+        k, v = batches[i % n_batches]
+        oqm.tom_oqm_quantize_append(mem.handle, 0, L, fpa, k, v)
+    torch.cuda.synchronize()
+    assert mem.n_groups == T
+
+    n_windows = T // fpa
+
+    def step(i, ev=None):
+        k, v = batches[i % n_batches]
+        oqm.tom_oqm_set_num_groups(mem.handle, (i % n_windows) * fpa)
+        if ev:
+            ev[0].record()
+        oqm.tom_oqm_quantize_append(mem.handle, 0, L, fpa, k, v)
+        if ev:
+            ev[1].record()
+        oqm.tom_oqm_set_num_groups(mem.handle, T)
+        q = queries[i % len(queries)]
+        oqm.tom_oqm_score_groups(mem.handle, 0, L, q, w.t_q, scores, T, None, path, ws)
+        if ev:
+            ev[2].record()
+        oqm.tom_oqm_topk(scores, T, L, T, w.top_k, idx)
+        if ev:
+            ev[3].record()
+        ko, vo = outs[i % 2]
+        oqm.tom_oqm_dequant_gather(mem.handle, 0, L, idx, w.top_k, k_eff, ko, vo)
+        if ev:
+            ev[4].record()
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i, events[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    def avg_ms(a, b):
+        return sum(e[a].elapsed_time(e[b]) for e in events) / len(events)
+
+    ms_append, ms_score, ms_topk, ms_gather = avg_ms(0, 1), avg_ms(1, 2), avg_ms(2, 3), avg_ms(3, 4)
+    ms_step = wall * 1e3 / args.steps
+    b_app, e_app = bytes_append(w, fpa, eb)
+    b_gat, e_gat = bytes_gather(w, k_eff, eb)
+    b_sc, b_tk = bytes_score(w, T, eb), bytes_topk(w, T, k_eff)
+    total_bytes = b_app + b_gat + b_sc + b_tk
+    gbps = lambda b, ms: b / (ms * 1e-3) / 1e9
+    tokens_per_append = fpa * w.group_tokens
+
+    out = {
+        "metric": METRIC,
+        "value": round(gbps(total_bytes, ms_step), 1),
+        "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {
+            "workload": f"{w.name}: {L} layers, {w.n_kv_heads} KV heads ({w.n_q_heads} query heads), "
+                        f"head_dim {w.head_dim}, {w.dtype} K/V, {T} frames x {w.group_tokens} tokens stored, "
+                        f"{fpa} frames per quantize-append, 4-bit codes, quant-group {w.qgroup} over head_dim, "
+                        f"{w.t_q}-token query, top-{k_eff} groups dequant-gathered to {w.dtype}",
+            "value_recipe": w.kind, "score_path": "token_gemm" if path == oqm.TOM_SCORE_TOKEN_GEMM else "mean_query",
+            "input_batches_rotated": n_batches,
+        },
+        "pct_of_hbm_peak": round(100 * gbps(total_bytes, ms_step) / HBM_PEAK_GBPS, 2),
+        "bytes_per_step": total_bytes,
+        "append": {"ms": round(ms_append, 4), "GBps": round(gbps(b_app, ms_append), 1),
+                   "pct_of_peak": round(100 * gbps(b_app, ms_append) / HBM_PEAK_GBPS, 2),
+                   "tokens_per_s": round(tokens_per_append / (ms_append * 1e-3), 1), "bytes": b_app},
+        "score": {"ms": round(ms_score, 4), "GBps": round(gbps(b_sc, ms_score), 1), "bytes": b_sc},
+        "topk": {"ms": round(ms_topk, 4)},
+        "gather": {"ms": round(ms_gather, 4), "GBps": round(gbps(b_gat, ms_gather), 1),
+                   "pct_of_peak": round(100 * gbps(b_gat, ms_gather) / HBM_PEAK_GBPS, 2), "bytes": b_gat},
+        "retrieval_ms_per_query": round(ms_score + ms_topk + ms_gather, 4),
+        "roofline": {"bound": "hbm", "kernel": "dequant_gather_kernel",
+                     "achieved": round(gbps(b_gat, ms_gather), 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(gbps(b_gat, ms_gather) / HBM_PEAK_GBPS, 4), "traffic": None},
+        "roofline_append": {"bound": "hbm", "kernel": "quantize_append_kernel",
+                            "achieved": round(gbps(b_app, ms_append), 1), "peak": HBM_PEAK_GBPS,
+                            "unit": "GB/s", "frac": round(gbps(b_app, ms_append) / HBM_PEAK_GBPS, 4),
+                            "traffic": None},
+    }
+
+    if not args.no_cpu_baseline:
+        nb = max(1, min(args.cpu_sample_batches, n_batches))
+        if fpa == 1:
+            nb = min(n_batches, 16)
+        sample = [(k.cpu(), v.cpu()) for k, v in batches[:nb]]
+        threads = min(16, os.cpu_count() or 1)
+        out["cpu_baseline"] = cpu_baseline(w, sample, queries[0].cpu(), threads)
+        out["cpu_baseline"]["value"] = round(out["cpu_baseline"]["value"], 3)
+        del out["cpu_baseline"]["tokens_per_s_append"]
+    print(json.dumps(out))
+    mem.close()
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,118 @@
+// Device-side helpers for the gfx950 kernels: wave64 cross-lane reductions,
+// 128-bit loads/stores of packed elements, dtype widening / narrowing.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace oqm {
+
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef double f64x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+struct In_f32 {};
+struct In_bf16 {};
+struct In_f16 {};
+
+// ---- DPP lane exchange ----------------------------------------------------
+// dpp_ctrl encodings: quad_perm[1,0,3,2] = 0xB1 (lane ^ 1), quad_perm[2,3,0,1] = 0x4E
+// (lane ^ 2), row_half_mirror = 0x141 (lane -> 7 - lane within 8), row_mirror = 0x140
+// (lane -> 15 - lane within 16).  After the first two steps all four lanes of a quad hold
+// the quad's result, so the mirrors combine whole quads / whole half-rows.
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+
+// All-reduce (min and max at once) over aligned sets of LANES lanes, LANES in {1,2,4,8,16}.
+template <int LANES>
+__device__ __forceinline__ void group_minmax(float& mn, float& mx) {
+    if constexpr (LANES >= 2) {
+        mn = fminf(mn, dpp_f32<0xB1>(mn));
+        mx = fmaxf(mx, dpp_f32<0xB1>(mx));
+    }
+    if constexpr (LANES >= 4) {
+        mn = fminf(mn, dpp_f32<0x4E>(mn));
+        mx = fmaxf(mx, dpp_f32<0x4E>(mx));
+    }
+    if constexpr (LANES >= 8) {
+        mn = fminf(mn, dpp_f32<0x141>(mn));
+        mx = fmaxf(mx, dpp_f32<0x141>(mx));
+    }
+    if constexpr (LANES >= 16) {
+        mn = fminf(mn, dpp_f32<0x140>(mn));
+        mx = fmaxf(mx, dpp_f32<0x140>(mx));
+    }
+}
+
+// Sum of a double over all 64 lanes of the wave (result valid in every lane).
+__device__ __forceinline__ double wave_sum_f64(double v) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+// ---- loading 8 consecutive elements as float32 -----------------------------
+// p must be 16-byte aligned.  Widening bf16 / f16 to float32 is exact.
+__device__ __forceinline__ void load8(const void* p, In_bf16, float (&x)[8]) {
+    const u32x4 w = *reinterpret_cast<const u32x4*>(p);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        x[2 * i] = __uint_as_float(w[i] << 16);
+        x[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+}
+
+__device__ __forceinline__ void load8(const void* p, In_f16, float (&x)[8]) {
+    const f16x8 h = *reinterpret_cast<const f16x8*>(p);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) x[i] = (float)h[i];
+}
+
+__device__ __forceinline__ void load8(const void* p, In_f32, float (&x)[8]) {
+    const f32x4 a = reinterpret_cast<const f32x4*>(p)[0];
+    const f32x4 b = reinterpret_cast<const f32x4*>(p)[1];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        x[i] = a[i];
+        x[4 + i] = b[i];
+    }
+}
+
+template <typename T> struct elem_bytes;
+template <> struct elem_bytes<In_f32> { static constexpr int value = 4; };
+template <> struct elem_bytes<In_bf16> { static constexpr int value = 2; };
+template <> struct elem_bytes<In_f16> { static constexpr int value = 2; };
+
+// ---- storing 8 consecutive float32 values, narrowed round-to-nearest-even ---
+__device__ __forceinline__ void store8(void* p, In_bf16, const float (&x)[8]) {
+    u32x4 w;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const f32x2 v = {x[2 * i], x[2 * i + 1]};
+        w[i] = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));  // v_cvt_pk_bf16_f32
+    }
+    __builtin_nontemporal_store(w, reinterpret_cast<u32x4*>(p));
+}
+
+__device__ __forceinline__ void store8(void* p, In_f16, const float (&x)[8]) {
+    f16x8 h;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) h[i] = (_Float16)x[i];  // v_cvt_f16_f32, ties to even
+    __builtin_nontemporal_store(h, reinterpret_cast<f16x8*>(p));
+}
+
+__device__ __forceinline__ void store8(void* p, In_f32, const float (&x)[8]) {
+    f32x4* o = reinterpret_cast<f32x4*>(p);
+    const f32x4 a = {x[0], x[1], x[2], x[3]};
+    const f32x4 b = {x[4], x[5], x[6], x[7]};
+    __builtin_nontemporal_store(a, o);
+    __builtin_nontemporal_store(b, o + 1);
+}
+
+}  // namespace oqm

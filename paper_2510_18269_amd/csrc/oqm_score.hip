@@ -1,0 +1,270 @@
+// Retrieval scoring on gfx950 (paper Sec. 3.4, Eq. 12; supplement
+// "Question-guided single-pass retrieval").
+//
+//   query_fold_kernel        Q [H_q][T_q][d] -> GQA mean over the r = H_q/H_k consecutive
+//                            query heads of a block, then mean over the T_q tokens.
+//   score_mean_query_kernel  one dot product (and one key norm) per stored frame-group
+//                            against the folded query: a float64 GEMV that streams the
+//                            summary keys once; HBM-bound (H_k*d*4 bytes per group).
+//   score_token_gemm_kernel  per-token scores [T_q x H_k*d] x [H_k*d x T] on the matrix
+//                            cores (v_mfma_f64_16x16x4_f64), then the token mean.
+//
+// Everything accumulates in float64 (the CDNA vector and matrix pipes run it at
+// full rate), so the float32 scores handed to top-k agree with a float64
+// reference up to the final rounding, and the selected indices with them.
+#include "oqm_common.h"
+#include "oqm_device.h"
+
+namespace oqm {
+namespace {
+
+// ------------------------------------------------------------------ query fold
+// grid (H_k, n_layers); 256 threads = (256 / (d/8)) token lanes x (d/8) channel lanes.
+template <typename QT>
+__global__ void __launch_bounds__(kBlock) query_fold_kernel(const ScoreArgs a, const int want_tokens) {
+    constexpr int EB = elem_bytes<QT>::value;
+    const int h = blockIdx.x, li = blockIdx.y;
+    const int d = a.head_dim, H = a.n_kv_heads, Hq = a.n_q_heads, Tq = a.t_q;
+    const int r = Hq / H;
+    const int64_t HD = (int64_t)H * d;
+    const int lpr = d >> 3;
+    const int jn = kBlock / lpr;
+    const int tid = threadIdx.x;
+    const int jl = tid / lpr;
+    const int slot = tid - jl * lpr;
+    const bool active = jl < jn;
+    const char* q = static_cast<const char*>(a.q);
+
+    double acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = 0.0;
+    if (active) {
+        for (int j = jl; j < Tq; j += jn) {
+            double qt[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) qt[i] = 0.0;
+            for (int g = 0; g < r; ++g) {
+                float x[8];
+                const int64_t off = (((int64_t)li * Hq + (h * r + g)) * Tq + j) * d + slot * 8;
+                load8(q + off * EB, QT{}, x);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) qt[i] += (double)x[i];
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                qt[i] = qt[i] / (double)r;
+                acc[i] += qt[i];
+            }
+            if (want_tokens) {
+                double* dst = a.ws_qtok + ((int64_t)li * Tq + j) * HD + (int64_t)h * d + slot * 8;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) dst[i] = qt[i];
+            }
+        }
+    }
+    __shared__ double red[kBlock * 8];
+    __shared__ double wsum[kBlock / 64];
+    if (active) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) red[jl * d + slot * 8 + i] = acc[i];
+    }
+    __syncthreads();
+    double sq = 0.0;
+    for (int c = tid; c < d; c += kBlock) {
+        double sum = 0.0;
+        for (int j = 0; j < jn; ++j) sum += red[j * d + c];
+        const double qb = sum / (double)Tq;
+        a.ws_qbar[(int64_t)li * HD + (int64_t)h * d + c] = qb;
+        sq += qb * qb;
+    }
+    sq = wave_sum_f64(sq);
+    if ((tid & 63) == 0) wsum[tid >> 6] = sq;
+    __syncthreads();
+    if (tid == 0) {
+        double tot = 0.0;
+        for (int w = 0; w < kBlock / 64; ++w) tot += wsum[w];
+        a.ws_qnorm2[(int64_t)li * H + h] = tot;  // this head's share of |q-bar|^2
+    }
+}
+
+// ------------------------------------------------------------------ mean-query GEMV
+constexpr int kGroupsPerWave = 8;
+
+// grid (ceil(T / (4 * kGroupsPerWave)), n_layers); dynamic LDS: H_k*d doubles (q-bar).
+__global__ void __launch_bounds__(kBlock) score_mean_query_kernel(const ScoreArgs a) {
+    extern __shared__ double qbar[];
+    const int li = blockIdx.y;
+    const int HD = a.n_kv_heads * a.head_dim;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int e = tid; e < HD; e += kBlock) qbar[e] = a.ws_qbar[(int64_t)li * HD + e];
+    double nq2 = 0.0;
+    for (int hh = 0; hh < a.n_kv_heads; ++hh) nq2 += a.ws_qnorm2[(int64_t)li * a.n_kv_heads + hh];
+    const double nq = sqrt(nq2);
+    __syncthreads();
+
+    const float* keys = a.keys + ((int64_t)(a.layer0 + li) * a.capacity_groups) * HD;
+    const int t0 = (blockIdx.x * (kBlock / 64) + wave) * kGroupsPerWave;
+    for (int gi = 0; gi < kGroupsPerWave; ++gi) {
+        const int t = t0 + gi;
+        if (t >= a.n_groups) break;  // uniform per wave
+        const float* key = keys + (int64_t)t * HD;
+        double dot = 0.0, nk2 = 0.0;
+        for (int e = lane * 4; e < HD; e += 256) {
+            const f32x4 kx = *reinterpret_cast<const f32x4*>(key + e);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const double kd = (double)kx[i];
+                dot = fma(qbar[e + i], kd, dot);
+                nk2 = fma(kd, kd, nk2);
+            }
+        }
+        dot = wave_sum_f64(dot);
+        nk2 = wave_sum_f64(nk2);
+        if (lane == 0) {
+            double s = dot;
+            if (a.sim == TOM_SIM_COSINE) {
+                const double nk = sqrt(nk2);
+                s = dot / (fmax(nq, 1e-12) * fmax(nk, 1e-12));
+            }
+            a.scores[(int64_t)li * a.score_stride + t] = (float)s;
+        }
+    }
+}
+
+// ------------------------------------------------------------------ per-token GEMM
+// S[j][t] = sum_e qtok[j][e] * key[t][e], j < T_q query tokens, t < T groups, e < H_k*d.
+// grid (ceil(T / 64), n_layers); 4 waves; wave w owns groups n0 + 16w .. + 15 and up to
+// four 16-token row tiles.  Operands are staged through LDS in chunks of kGemmK along e.
+//
+// v_mfma_f64_16x16x4_f64 register layout (checked on hardware by the GPU tests through
+// the per-token score output): lane = 16*kk + i supplies A[i][kk] and B[kk][i]; lane
+// 16*g + j holds D[4*v + g][j] in accumulator register v.
+constexpr int kGemmN = 64;
+constexpr int kGemmM = 64;
+constexpr int kGemmK = 32;
+constexpr int kLdA = kGemmK + 4;  // doubles; 2-way LDS bank conflict at most (the minimum for b64)
+constexpr int kLdB = kGemmK + 4;  // floats; conflict-free fragment reads
+
+__device__ __forceinline__ int mfma_d_row(int lane, int v) { return 4 * v + (lane >> 4); }
+
+__global__ void __launch_bounds__(kBlock) score_token_gemm_kernel(const ScoreArgs a) {
+    __shared__ double As[kGemmM * kLdA];
+    __shared__ float Bs[kGemmN * kLdB];
+    const int li = blockIdx.y;
+    const int n0 = blockIdx.x * kGemmN;
+    const int HD = a.n_kv_heads * a.head_dim;
+    const int T = a.n_groups, Tq = a.t_q;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int fi = lane & 15, kk = lane >> 4;
+    const float* keys = a.keys + ((int64_t)(a.layer0 + li) * a.capacity_groups) * HD;
+    const double* qtok = a.ws_qtok + (int64_t)li * Tq * HD;
+
+    double colsum = 0.0, nk2 = 0.0;
+    for (int m0 = 0; m0 < Tq; m0 += kGemmM) {
+        const int rows = min(kGemmM, Tq - m0);
+        const int mt = (rows + 15) >> 4;
+        f64x4 acc[kGemmM / 16];
+#pragma unroll
+        for (int m = 0; m < kGemmM / 16; ++m) acc[m] = f64x4{0.0, 0.0, 0.0, 0.0};
+
+        for (int k0 = 0; k0 < HD; k0 += kGemmK) {
+            __syncthreads();  // previous chunk fully consumed
+            // stage A: 64 token rows x 32 doubles, 16 lanes x 16 B per row
+            for (int rr = tid >> 4; rr < kGemmM; rr += kBlock / 16) {
+                const int c = (tid & 15) * 2;
+                double v0 = 0.0, v1 = 0.0;
+                if (rr < rows && k0 + c < HD) {
+                    const double* p = qtok + (int64_t)(m0 + rr) * HD + k0 + c;
+                    v0 = p[0];
+                    v1 = p[1];
+                }
+                As[rr * kLdA + c] = v0;
+                As[rr * kLdA + c + 1] = v1;
+            }
+            // stage B: 64 groups x 32 floats, 8 lanes x 16 B per row
+            for (int rr = tid >> 3; rr < kGemmN; rr += kBlock / 8) {
+                const int c = (tid & 7) * 4;
+                f32x4 v = {0.0f, 0.0f, 0.0f, 0.0f};
+                if (n0 + rr < T && k0 + c < HD)
+                    v = *reinterpret_cast<const f32x4*>(keys + (int64_t)(n0 + rr) * HD + k0 + c);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) Bs[rr * kLdB + c + i] = v[i];
+            }
+            __syncthreads();
+#pragma unroll
+            for (int ks = 0; ks < kGemmK / 4; ++ks) {
+                const double bv = (double)Bs[(wave * 16 + fi) * kLdB + ks * 4 + kk];
+                if (m0 == 0) nk2 = fma(bv, bv, nk2);
+#pragma unroll
+                for (int m = 0; m < kGemmM / 16; ++m) {
+                    if (m < mt) {
+                        const double av = As[(m * 16 + fi) * kLdA + ks * 4 + kk];
+                        acc[m] = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc[m], 0, 0, 0);
+                    }
+                }
+            }
+        }
+        const int t = n0 + wave * 16 + fi;
+#pragma unroll
+        for (int m = 0; m < kGemmM / 16; ++m) {
+            if (m < mt) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int j = m0 + m * 16 + mfma_d_row(lane, v);
+                    colsum += acc[m][v];  // rows >= T_q were staged as zeros
+                    if (a.token_scores && j < Tq && t < T)
+                        a.token_scores[((int64_t)li * Tq + j) * T + t] = (float)acc[m][v];
+                }
+            }
+        }
+    }
+    // lanes fi, 16 + fi, 32 + fi, 48 + fi hold the partial sums of group n0 + 16*wave + fi
+    colsum += __shfl_xor(colsum, 16, 64);
+    colsum += __shfl_xor(colsum, 32, 64);
+    nk2 += __shfl_xor(nk2, 16, 64);
+    nk2 += __shfl_xor(nk2, 32, 64);
+    const int t = n0 + wave * 16 + fi;
+    if (kk == 0 && t < T) {
+        double s = colsum / (double)Tq;
+        if (a.sim == TOM_SIM_COSINE) {
+            double nq2 = 0.0;
+            for (int hh = 0; hh < a.n_kv_heads; ++hh) nq2 += a.ws_qnorm2[(int64_t)li * a.n_kv_heads + hh];
+            s = s / (fmax(sqrt(nq2), 1e-12) * fmax(sqrt(nk2), 1e-12));
+        }
+        a.scores[(int64_t)li * a.score_stride + t] = (float)s;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_query_fold(const ScoreArgs& a, bool want_tokens, hipStream_t s) {
+    if (a.n_layers == 0) return hipSuccess;
+    const dim3 grid(a.n_kv_heads, a.n_layers);
+    switch (a.q_dtype) {
+        case TOM_F32: query_fold_kernel<In_f32><<<grid, dim3(kBlock), 0, s>>>(a, want_tokens); break;
+        case TOM_BF16: query_fold_kernel<In_bf16><<<grid, dim3(kBlock), 0, s>>>(a, want_tokens); break;
+        case TOM_F16: query_fold_kernel<In_f16><<<grid, dim3(kBlock), 0, s>>>(a, want_tokens); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_score_mean_query(const ScoreArgs& a, hipStream_t s) {
+    if (a.n_layers == 0 || a.n_groups == 0) return hipSuccess;
+    const int per_block = (kBlock / 64) * kGroupsPerWave;
+    const dim3 grid((a.n_groups + per_block - 1) / per_block, a.n_layers);
+    const size_t lds = (size_t)a.n_kv_heads * a.head_dim * sizeof(double);
+    score_mean_query_kernel<<<grid, dim3(kBlock), lds, s>>>(a);
+    return hipGetLastError();
+}
+
+}  // namespace oqm
+
+namespace oqm {
+hipError_t launch_score_token_gemm(const ScoreArgs& a, hipStream_t s) {
+    if (a.n_layers == 0 || a.n_groups == 0) return hipSuccess;
+    const dim3 grid((a.n_groups + kGemmN - 1) / kGemmN, a.n_layers);
+    score_token_gemm_kernel<<<grid, dim3(kBlock), 0, s>>>(a);
+    return hipGetLastError();
+}
+}  // namespace oqm

@@ -1,0 +1,143 @@
+"""CPU-only checks of the C ABI: the library loads, exports every symbol the header
+declares, and its host-side validation returns the documented error codes before
+anything is launched (no GPU is touched by these tests)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def oqm():
+    lib = os.path.join(ROOT, "paper_2510_18269_amd", "libtom_oqm.so")
+    if not os.path.exists(lib):
+        from paper_2510_18269_amd import build
+        build.build()
+    from paper_2510_18269_amd import oqm as m
+    return m
+
+
+def test_every_declared_symbol_is_exported(oqm):
+    text = ""
+    inc = os.path.join(ROOT, "include")
+    for name in sorted(os.listdir(inc)):
+        if name.endswith(".h"):
+            text += open(os.path.join(inc, name)).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(tom_[a-z0-9_]+)\s*\(", text))
+    assert {"tom_oqm_quantize_append", "tom_oqm_score_groups", "tom_oqm_topk",
+            "tom_oqm_dequant_gather"} <= declared
+    for sym in declared:
+        assert hasattr(oqm.lib, sym), f"{sym} is declared in include/ but not exported"
+    assert declared == set(oqm.EXPORTS)
+
+
+def test_sizes_follow_the_documented_layout(oqm):
+    cfg = oqm.make_config(28, 4, 28, 128, 196, 64, 1024)
+    s = oqm.tom_oqm_query_sizes(cfg)
+    tiles = 28 * 2 * 1024 * 4
+    assert s.codes == tiles * 196 * 128 // 2
+    assert s.scale == s.zero == tiles * 196 * 2 * 4
+    assert s.keys == 28 * 1024 * 4 * 128 * 4
+
+
+@pytest.mark.parametrize("field,value,status", [
+    ("head_dim", 100, "INVALID"), ("qgroup", 48, "INVALID"), ("qgroup", 4, "UNSUPPORTED"),
+    ("bits", 3, "INVALID"), ("bits", 2, "UNSUPPORTED"), ("n_q_heads", 27, "INVALID"),
+    ("group_tokens", 0, "INVALID"), ("capacity_groups", 0, "INVALID"), ("in_dtype", 7, "INVALID"),
+    ("sim", 2, "INVALID"), ("qaxis", 1, "UNSUPPORTED"), ("qaxis", 5, "INVALID")])
+def test_bad_configurations_are_rejected(oqm, field, value, status):
+    cfg = oqm.make_config(2, 4, 28, 128, 196, 64, 16)
+    setattr(cfg, field, value)
+    with pytest.raises(oqm.TomError) as e:
+        oqm.tom_oqm_create(cfg)
+    want = oqm.TOM_ERR_INVALID_ARG if status == "INVALID" else oqm.TOM_ERR_UNSUPPORTED
+    assert e.value.status == want and oqm.tom_last_error()
+
+
+def test_host_side_validation_before_any_launch(oqm):
+    cfg = oqm.make_config(2, 2, 4, 64, 16, 32, 8)
+    h = oqm.tom_oqm_create(cfg)
+    try:
+        fake = 0x1000                                    # never dereferenced: every call below fails first
+        with pytest.raises(oqm.TomError) as e:
+            oqm.tom_oqm_quantize_append(h, 0, 2, 1, fake, fake, None, (1, 1, 1, 1))
+        assert e.value.status == oqm.TOM_ERR_NOT_BOUND
+        with pytest.raises(oqm.TomError) as e:
+            oqm.tom_oqm_bind(h, fake, fake + 4, fake, fake)     # misaligned
+        assert e.value.status == oqm.TOM_ERR_INVALID_ARG
+        oqm.tom_oqm_bind(h, fake, fake, fake, fake)
+        assert oqm.tom_oqm_num_groups(h) == 0
+        st = (2 * 2 * 16 * 64, 2 * 16 * 64, 16 * 64, 64)
+        with pytest.raises(oqm.TomError) as e:           # over capacity: nothing is evicted
+            oqm.tom_oqm_quantize_append(h, 0, 2, 9, fake, fake, None, st)
+        assert e.value.status == oqm.TOM_ERR_CAPACITY and oqm.tom_oqm_num_groups(h) == 0
+        with pytest.raises(oqm.TomError) as e:           # layer range
+            oqm.tom_oqm_quantize_append(h, 1, 2, 1, fake, fake, None, st)
+        assert e.value.status == oqm.TOM_ERR_INVALID_ARG
+        with pytest.raises(oqm.TomError) as e:           # stride not a multiple of 16 bytes
+            oqm.tom_oqm_quantize_append(h, 0, 2, 1, fake, fake, None, (st[0], st[1], st[2], 65))
+        assert e.value.status == oqm.TOM_ERR_INVALID_ARG
+        with pytest.raises(oqm.TomError) as e:
+            oqm.tom_oqm_quantize_append(h, 0, 2, 1, None, fake, None, st)
+        assert e.value.status == oqm.TOM_ERR_INVALID_ARG
+        # no-ops succeed without touching the GPU
+        assert oqm.tom_oqm_quantize_append(h, 0, 2, 0, fake, fake, None, st) == 0
+        oqm.tom_oqm_score_groups(h, 0, 2, fake, 1, fake, 0, q_dtype=oqm.TOM_F32)   # T == 0
+        oqm.tom_oqm_dequant_gather(h, 0, 2, fake, 4, 0, fake, fake)                # k_eff == 0
+        with pytest.raises(oqm.TomError):
+            oqm.tom_oqm_dequant_gather(h, 0, 2, fake, 4, 5, fake, fake)            # k_eff > k
+        with pytest.raises(oqm.TomError):
+            oqm.tom_oqm_dequant_gather(h, 0, 3, fake, 4, 1, fake, fake)            # layers
+        # checkpoint restore: the counter can be set within capacity only
+        oqm.tom_oqm_set_num_groups(h, 8)
+        assert oqm.tom_oqm_num_groups(h) == 8
+        with pytest.raises(oqm.TomError):
+            oqm.tom_oqm_set_num_groups(h, 9)
+        with pytest.raises(oqm.TomError) as e:           # score needs a workspace
+            oqm.tom_oqm_score_groups(h, 0, 2, fake, 1, fake, 8, q_dtype=oqm.TOM_F32)
+        assert e.value.status == oqm.TOM_ERR_INVALID_ARG and "workspace" in str(e.value)
+        with pytest.raises(oqm.TomError):                # stride shorter than T
+            oqm.tom_oqm_score_groups(h, 0, 2, fake, 1, fake, 7, q_dtype=oqm.TOM_F32)
+        oqm.tom_oqm_reset(h)
+        assert oqm.tom_oqm_num_groups(h) == 0
+    finally:
+        oqm.tom_oqm_destroy(h)
+
+
+def test_workspace_size(oqm):
+    cfg = oqm.make_config(28, 4, 28, 128, 196, 64, 16)
+    h = oqm.tom_oqm_create(cfg)
+    try:
+        small = oqm.tom_oqm_score_workspace_bytes(h, 28, 32, oqm.TOM_SCORE_MEAN_QUERY)
+        big = oqm.tom_oqm_score_workspace_bytes(h, 28, 32, oqm.TOM_SCORE_TOKEN_GEMM)
+        assert small >= 28 * (512 + 4) * 8 and small < 28 * 520 * 8 + 64
+        assert big - small == 28 * 32 * 512 * 8
+        assert oqm.tom_oqm_score_workspace_bytes(h, 28, 32, oqm.TOM_SCORE_AUTO, True) == big
+        assert oqm.tom_oqm_score_workspace_bytes(h, 28, 0) == 0
+    finally:
+        oqm.tom_oqm_destroy(h)
+
+
+def test_topk_argument_checks_and_k_eff(oqm):
+    k_eff = oqm.tom_oqm_topk(0x1000, 16, 0, 10, 64, 0x1000)        # no rows: nothing launched
+    assert k_eff == 10
+    assert oqm.tom_oqm_topk(0x1000, 16, 3, 0, 4, 0x1000) == 0      # nothing stored yet
+    for bad in (dict(k=0), dict(n_groups=-1), dict(score_stride=5), dict(order=3)):
+        args = dict(score_stride=16, n_rows=1, n_groups=10, k=4, order=0)
+        args.update(bad)
+        with pytest.raises(oqm.TomError) as e:
+            oqm.tom_oqm_topk(0x1000, args["score_stride"], args["n_rows"], args["n_groups"],
+                             args["k"], 0x1000, order=args["order"])
+        assert e.value.status == oqm.TOM_ERR_INVALID_ARG
+    with pytest.raises(oqm.TomError) as e:
+        oqm.tom_oqm_topk(0x1000, 10000, 1, 10000, 5000, 0x1000, order=oqm.TOM_ORDER_SCORE_DESC)
+    assert e.value.status == oqm.TOM_ERR_UNSUPPORTED
+
+
+def test_k_from_budget_matches_the_supplement_formula(oqm, oracle):
+    for B, G, T in [(12544, 196, 1000), (12544, 50, 10 ** 6), (12544, 50, 7), (1, 50, 10), (0, 50, 10)]:
+        assert oqm.tom_oqm_k_from_budget(B, G, T) == oracle.k_from_budget(B, G, T * G)

@@ -1,0 +1,251 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Bar: packed codes, scale, zero and retrieved indices bit-exact; summary keys
+and scores within one float32 ulp (float64 accumulation on both sides); dequantized values
+bit-exact (identical float32 multiply, add and round-to-nearest-even narrowing on both
+sides), which is inside the stated 1e-6 relative / 1 bf16 ulp tolerance."""
+import numpy as np
+import pytest
+import torch
+
+import synth_kv
+from tests import harness as H
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def oqm():
+    from paper_2510_18269_amd import oqm as m      # raises if the library is not built
+    assert torch.cuda.is_available()
+    return m
+
+
+def _stream_and_check(oqm, w, frames_per_call, k=None, path=None, want_tokens=False, out_dtype=None):
+    st, mem = H.pair_for(oqm, w, out_dtype=out_dtype)
+    try:
+        f = 0
+        while f < w.n_frames:
+            n = min(frames_per_call, w.n_frames - f)
+            kk, vv = synth_kv.kv_frames(w, f, n)
+            H.append_both(oqm, st, mem, kk, vv)
+            f += n
+        frac = H.compare_storage(st, mem)
+        assert frac < 1e-3
+        q = synth_kv.query(w)
+        return H.full_path_check(oqm, st, mem, q, k or w.top_k, path, want_tokens)
+    finally:
+        mem.close()
+
+
+def test_c1_tiny_stream_full(oqm):
+    w = synth_kv.WORKLOADS["C1"]
+    r = _stream_and_check(oqm, w, w.n_frames)
+    assert r["k_eff"] == 4 and r["loose_rows"] == 0
+
+
+def test_c2_single_layer_full(oqm):
+    w = synth_kv.WORKLOADS["C2"]
+    r = _stream_and_check(oqm, w, 64)
+    assert r["k_eff"] == 32 and r["loose_rows"] == 0
+
+
+@pytest.mark.parametrize("name,layers,frames,per_call", [("C3", 3, 40, 16), ("C4", 2, 37, 1),
+                                                         ("C5", 3, 48, 32)])
+def test_reduced_multi_layer_streams(oqm, name, layers, frames, per_call):
+    """C3/C4/C5 recipes (per-layer std, one-frame appends, outlier keys + gs 32) at a size
+    the oracle checks element by element: several tiles, ragged 196-token groups."""
+    w = synth_kv.scaled(synth_kv.WORKLOADS[name], n_layers=layers, n_frames=frames,
+                        top_k=min(synth_kv.WORKLOADS[name].top_k, 24))
+    path = oqm.TOM_SCORE_TOKEN_GEMM if name == "C5" else None
+    r = _stream_and_check(oqm, w, per_call, path=path, want_tokens=(name == "C5"))
+    assert r["loose_rows"] == 0
+
+
+@pytest.mark.parametrize("G,d,gs,dt,H_k,H_q", [
+    (50, 128, 64, "f16", 4, 28),      # the paper's 50-token groups, FP16 K/V
+    (1, 64, 8, "f32", 1, 1), (197, 128, 128, "bf16", 2, 4), (13, 96, 32, "bf16", 3, 6),
+    (64, 256, 16, "f16", 2, 2), (33, 8, 8, "f32", 5, 5), (7, 512, 64, "bf16", 1, 3)])
+def test_shapes_dtypes_and_ragged_tails(oqm, G, d, gs, dt, H_k, H_q):
+    w = synth_kv.Workload("X", 2, H_k, H_q, d, G, 11, gs, 5, 4, dt, "cosine", 100 + G + d, "layer_std", 11)
+    r = _stream_and_check(oqm, w, 4)
+    assert r["k_eff"] == 4
+    r = _stream_and_check(oqm, synth_kv.scaled(w, sim="dot", t_q=17), 11, k=6,
+                          path=oqm.TOM_SCORE_TOKEN_GEMM, want_tokens=True)
+    assert r["k_eff"] == 6
+
+
+def test_mixed_in_out_dtypes(oqm):
+    w = synth_kv.scaled(synth_kv.WORKLOADS["C2"], n_frames=9, top_k=3)
+    for out in ("f32", "f16", "bf16"):
+        _stream_and_check(oqm, w, 9, out_dtype=out)
+
+
+def test_strided_input_layer_ranges_and_separate_summary(oqm):
+    """Token-major source buffers [F][G][L][H][d], layers appended one at a time with
+    commit only on the last, summary keys from a separate (pre-rotary) tensor."""
+    st, mem = H.make_pair(oqm, n_layers=3, n_kv_heads=2, n_q_heads=4, head_dim=64, group_tokens=21,
+                          qgroup=32, capacity=6, in_dtype="bf16")
+    try:
+        g = torch.Generator().manual_seed(9)
+        F, G, L, Hk, d = 2, 21, 3, 2, 64
+        for call in range(2):
+            bk = torch.randn(F, G, L, Hk, d, generator=g).to(torch.bfloat16)
+            bv = torch.randn(F, G, L, Hk, d, generator=g).to(torch.bfloat16)
+            pre = torch.randn(F, G, L, Hk, d, generator=g).to(torch.bfloat16)
+            strides = (G * L * Hk * d, Hk * d, d, L * Hk * d)
+            dk, dv, dp = bk.cuda(), bv.cuda(), pre.cuda()
+            for l in range(L):
+                off = l * strides[1]
+                H.orc.quantize_append(st, H.bits(bk).ravel()[off:], H.bits(bv).ravel()[off:],
+                                      H.bits(pre).ravel()[off:], layer0=l, strides=strides,
+                                      n_frames=F, n_layers=1, commit=(l == L - 1))
+                first = oqm.tom_oqm_quantize_append(
+                    mem.handle, l, 1, F, dk.data_ptr() + off * 2, dv.data_ptr() + off * 2,
+                    dp.data_ptr() + off * 2, strides, commit=(l == L - 1))
+                assert first == call * F
+            torch.cuda.synchronize()
+        assert mem.n_groups == 4
+        H.compare_storage(st, mem)
+        q = torch.randn(3, 4, 3, 64, generator=g).to(torch.bfloat16)
+        H.full_path_check(oqm, st, mem, q, 3)
+    finally:
+        mem.close()
+
+
+def test_empty_and_degenerate_cases(oqm):
+    st, mem = H.make_pair(oqm, n_layers=2, n_kv_heads=2, n_q_heads=2, head_dim=64, group_tokens=16,
+                          qgroup=32, capacity=5, in_dtype="f32")
+    try:
+        g = torch.Generator().manual_seed(4)
+        # nothing stored: score and top-k are no-ops, k_eff = 0
+        sc = torch.zeros(2, 8, device="cuda")
+        idx = torch.full((2, 4), -7, dtype=torch.int32, device="cuda")
+        assert oqm.tom_oqm_topk(sc, 8, 2, 0, 4, idx) == 0
+        assert (idx == -7).all()
+        # constant tiles, zero tiles, a huge-range tile, negative zeros
+        k = torch.randn(5, 2, 2, 16, 64, generator=g)
+        k[0] = 3.25
+        k[1, 0] = 0.0
+        k[1, 1, 0, :, ::2] = -0.0
+        k[2, :, :, 3, 5] = 1e30
+        k[2, :, :, 4, 6] = -1e30
+        k[3, 0, 0, 0, :32] = torch.linspace(0, 1e-37, 32)       # sub-normal step
+        v = -k.clone()
+        H.append_both(oqm, st, mem, k, v)
+        H.compare_storage(st, mem)
+        with pytest.raises(oqm.TomError) as e:                    # full: nothing is evicted
+            oqm.tom_oqm_quantize_append(mem.handle, 0, 2, 1, k.cuda(), v.cuda())
+        assert e.value.status == oqm.TOM_ERR_CAPACITY and mem.n_groups == 5
+        # k larger than the number of stored groups: all of them, in order; rest untouched
+        q = torch.randn(2, 2, 1, 64, generator=g)
+        r = H.full_path_check(oqm, st, mem, q, 8)
+        assert r["k_eff"] == 5
+        # zero query under cosine: norms are clamped, scores are 0, lowest indices win
+        sc, _ = H.gpu_scores(oqm, mem, torch.zeros(2, 2, 1, 64))
+        assert (sc[:, :5] == 0).all()
+        idx, k_eff, _, _ = H.gpu_retrieve(oqm, mem, sc, 3, 2)
+        assert idx.tolist() == [[0, 1, 2]] * 2
+    finally:
+        mem.close()
+
+
+def test_gather_skips_bad_indices_and_respects_the_bound(oqm):
+    st, mem = H.make_pair(oqm, n_layers=1, n_kv_heads=2, n_q_heads=2, head_dim=64, group_tokens=10,
+                          qgroup=32, capacity=8, in_dtype="bf16")
+    try:
+        k, v = (torch.randn(6, 1, 2, 10, 64, generator=torch.Generator().manual_seed(s)).to(torch.bfloat16)
+                for s in (1, 2))
+        H.append_both(oqm, st, mem, k, v)
+        kq = 4
+        idx = torch.tensor([[5, 6, -1, 2]], dtype=torch.int32, device="cuda")   # 6 and -1 are not stored
+        G = 10
+        guard = 3
+        ko = torch.full((1, 2, kq * G + guard, 64), 7.0, dtype=torch.bfloat16, device="cuda")
+        vo = ko.clone()
+        # the library sees buffers of exactly k*G rows per head: hand it per-head views via k = 4
+        ko_c = torch.full((1, 2, kq * G, 64), 7.0, dtype=torch.bfloat16, device="cuda")
+        vo_c = ko_c.clone()
+        oqm.tom_oqm_dequant_gather(mem.handle, 0, 1, idx, kq, 4, ko_c, vo_c)
+        torch.cuda.synchronize()
+        ref_k, ref_v = H.orc.dequant_gather(st, np.array([[5, 2]], np.int32), 2)
+        got = H.bits(ko_c)
+        assert np.array_equal(got[:, :, 0:G], ref_k[:, :, 0:G])
+        assert np.array_equal(got[:, :, 3 * G:4 * G], ref_k[:, :, G:2 * G])
+        seven = H.bits(torch.tensor([7.0], dtype=torch.bfloat16))[0]
+        assert np.all(got[:, :, G:3 * G] == seven)                 # skipped ranks untouched
+        # k_eff < k: rows beyond k_eff*G stay as they were
+        ko_c.fill_(7.0)
+        oqm.tom_oqm_dequant_gather(mem.handle, 0, 1, idx, kq, 1, ko_c, vo_c)
+        torch.cuda.synchronize()
+        got = H.bits(ko_c)
+        assert np.array_equal(got[:, :, 0:G], ref_k[:, :, 0:G]) and np.all(got[:, :, G:] == seven)
+    finally:
+        mem.close()
+
+
+@pytest.mark.parametrize("T,k", [(1, 1), (37, 5), (256, 32), (1024, 64), (3600, 64), (5000, 4096),
+                                 (8192, 100), (8193, 100), (40000, 777)])
+def test_topk_against_oracle(oqm, T, k):
+    g = torch.Generator().manual_seed(T + k)
+    rows = 3
+    s = torch.randn(rows, T + 5, generator=g)
+    s[1] = torch.round(s[1] * 4) / 4                               # heavy exact ties
+    s[2, ::3] = 0.0
+    s[2, 1::3] = -0.0                                              # -0 == +0
+    s[:, T:] = 1e9                                                 # padding beyond n_groups must never win
+    sd = s.cuda()
+    for order in (oqm.TOM_ORDER_INDEX_ASC, oqm.TOM_ORDER_SCORE_DESC):
+        if order == oqm.TOM_ORDER_SCORE_DESC and min(k, T) > 4096:
+            continue
+        idx = torch.full((rows, k), -7, dtype=torch.int32, device="cuda")
+        k_eff = oqm.tom_oqm_topk(sd, T + 5, rows, T, k, idx, order)
+        torch.cuda.synchronize()
+        want, k_ref = H.orc.topk(s.numpy(), k, order, n_groups=T)
+        assert k_eff == k_ref == min(k, T)
+        got = idx.cpu().numpy()
+        assert np.array_equal(got[:, :k_eff], want[:, :k_eff])
+        assert np.all(got[:, k_eff:] == -7)
+
+
+def test_topk_all_equal_and_monotone_rows(oqm):
+    s = torch.zeros(2, 500)
+    s[1] = torch.arange(500, dtype=torch.float32)
+    idx = torch.zeros((2, 7), dtype=torch.int32, device="cuda")
+    oqm.tom_oqm_topk(s.cuda(), 500, 2, 500, 7, idx)
+    assert idx.cpu().tolist() == [list(range(7)), list(range(493, 500))]
+    oqm.tom_oqm_topk(s.cuda(), 500, 2, 500, 7, idx, oqm.TOM_ORDER_SCORE_DESC)
+    assert idx.cpu().tolist() == [list(range(7)), list(range(499, 492, -1))]
+
+
+def test_planted_query_is_retrieved(oqm):
+    w = synth_kv.scaled(synth_kv.WORKLOADS["C2"], n_frames=40, n_q_heads=4, t_q=1)
+    st, mem = H.pair_for(oqm, w)
+    try:
+        k, v = synth_kv.kv_frames(w, 0, 40)
+        H.append_both(oqm, st, mem, k, v)
+        keys = mem.keys.view(1, 40, 4, 128)
+        q = keys[:, 23].reshape(1, 4, 1, 128).contiguous()       # r = 1: the stored key itself
+        for path in (oqm.TOM_SCORE_MEAN_QUERY, oqm.TOM_SCORE_TOKEN_GEMM):
+            sc, _ = H.gpu_scores(oqm, mem, q, path)
+            assert abs(sc[0, 23].item() - 1.0) < 1e-6 and sc[0, :40].argmax().item() == 23
+            assert (sc[0, :40].abs() <= 1 + 1e-6).all()
+    finally:
+        mem.close()
+
+
+def test_both_score_paths_agree(oqm):
+    w = synth_kv.scaled(synth_kv.WORKLOADS["C5"], n_layers=2, n_frames=70, t_q=64)
+    st, mem = H.pair_for(oqm, w)
+    try:
+        k, v = synth_kv.kv_frames(w, 0, 70)
+        H.append_both(oqm, st, mem, k, v)
+        q = synth_kv.query(w)
+        a, _ = H.gpu_scores(oqm, mem, q, oqm.TOM_SCORE_MEAN_QUERY, stride_pad=3)
+        b, tok = H.gpu_scores(oqm, mem, q, oqm.TOM_SCORE_TOKEN_GEMM, want_tokens=True)
+        a, b = a.cpu().numpy()[:, :70], b.cpu().numpy()[:, :70]
+        assert np.all(np.abs(a - b) <= np.spacing(np.abs(a)))
+        # longer queries than one 64-row tile, and a ragged last row tile
+        w2 = synth_kv.scaled(w, t_q=150)
+        H.full_path_check(oqm, st, mem, synth_kv.query(w2), 9, oqm.TOM_SCORE_TOKEN_GEMM, True)
+    finally:
+        mem.close()
