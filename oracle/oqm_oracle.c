@@ -32,7 +32,10 @@
  *
  * Readings taken where the paper is silent (each listed in the design notes):
  *   - rounding of "uint4(.)": round half to even, then clamp to [0, levels]
- *   - code = rne((x - m) * (1/s)) with 1/s computed once per quant-group
+ *   - code = rne(d * inv) with d = float32(x - m), inv = float32(1/s) computed once
+ *     per quant-group, and the product d * inv NOT rounded before the rounding to
+ *     an integer (one rounding instead of two)
+ *   - dequantized value = float32(code * s + m) with a single rounding
  *   - s < FLT_MIN (incl. max == min)  =>  s stored as 0, all codes 0
  *   - m = min + 0.0f so that a stored zero point is never -0
  *   - scale / zero stored as float32
@@ -212,10 +215,12 @@ static void quant_group(const float* x, int64_t stride, int n, int levels,
     *scale = s;
     *zero = mn;                                     /* Eq. 9: m = min */
     for (int i = 0; i < n; ++i) {
-        float t = (x[(int64_t)i * stride] - mn) * inv;
-        float r = nearbyintf(t);                    /* default mode: ties to even */
-        if (r < 0.0f) r = 0.0f;
-        if (r > (float)levels) r = (float)levels;
+        float diff = x[(int64_t)i * stride] - mn;   /* one float32 subtraction */
+        /* the product of two float32 values is exact in double, so this rounds the
+         * exact product (x - m) * (1/s) once, to the nearest integer, ties to even */
+        double r = nearbyint((double)diff * (double)inv);
+        if (r < 0.0) r = 0.0;
+        if (r > (double)levels) r = (double)levels;
         c[(int64_t)i * cstride] = (uint8_t)r;
     }
 }
@@ -271,8 +276,8 @@ int32_t tomref_quantize_tile(const float* x, int32_t G, int32_t d, int32_t gs, i
     return 0;
 }
 
-/* Eq. 11 on one head tile: x_hat = float(code) * s + m, separate multiply and
- * add, both rounded to float32. */
+/* Eq. 11 on one head tile: x_hat = float(code) * s + m evaluated exactly and
+ * rounded once to float32 (a fused multiply-add). */
 int32_t tomref_dequant_tile(const uint8_t* packed, const float* scale, const float* zero,
                             int32_t G, int32_t d, int32_t gs, int32_t qaxis, int32_t bits,
                             float* out) {
@@ -285,8 +290,7 @@ int32_t tomref_dequant_tile(const uint8_t* packed, const float* scale, const flo
             int64_t e = (int64_t)tok * d + ch;
             unsigned code = (packed[e / per_byte] >> ((e % per_byte) * bits)) & mask;
             int64_t mi = (qaxis == TOMREF_QAXIS_HEAD_DIM) ? (int64_t)tok * ng + ch / gs : ch;
-            float p = (float)code * scale[mi];
-            out[e] = p + zero[mi];
+            out[e] = fmaf((float)code, scale[mi], zero[mi]);   /* code*s + m, rounded once */
         }
     return 0;
 }

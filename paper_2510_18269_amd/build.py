@@ -11,6 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libtom_oqm.so")
 OBJ = os.path.join(HERE, "_build")
+SELFCHECK = os.path.join(HERE, "selfcheck_division.bin")
 
 SOURCES = ["oqm_api.hip", "oqm_quantize.hip", "oqm_dequant.hip", "oqm_score.hip", "oqm_topk.hip"]
 
@@ -41,6 +42,13 @@ def build(verbose: bool = False) -> str:
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stdout}\n{r.stderr}")
+    # stand-alone GPU program that checks the kernels' division shortcuts exhaustively
+    cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-ffp-contract=off",
+           "-Wno-unused-result", "-I", INCLUDE, "-I", CSRC,
+           os.path.join(CSRC, "selfcheck_division.hip"), "-o", SELFCHECK]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"selfcheck build failed:\n{r.stdout}\n{r.stderr}")
     return LIB
 
 

@@ -34,6 +34,8 @@ static tom_status_t check_config(const tom_oqm_config_t* c) {
     if (c->head_dim < 8 || c->head_dim % 8 || c->head_dim > 2048)
         return fail(TOM_ERR_INVALID_ARG, "head_dim %d must be a multiple of 8 in [8, 2048]", c->head_dim);
     if (c->group_tokens < 1) return fail(TOM_ERR_INVALID_ARG, "group_tokens must be >= 1");
+    if (((int64_t)c->group_tokens + 1024) * c->head_dim * 4 >= (1LL << 31))
+        return fail(TOM_ERR_UNSUPPORTED, "group_tokens * head_dim is too large (one head tile must stay below 2 GiB)");
     if (c->capacity_groups < 1) return fail(TOM_ERR_INVALID_ARG, "capacity_groups must be >= 1");
     if (!dtype_ok(c->in_dtype) || !dtype_ok(c->out_dtype))
         return fail(TOM_ERR_INVALID_ARG, "in_dtype / out_dtype must be TOM_F32, TOM_BF16 or TOM_F16");
@@ -160,6 +162,8 @@ tom_status_t tom_oqm_quantize_append(tom_oqm_t* h, int32_t layer0, int32_t n_lay
         return fail(TOM_ERR_INVALID_ARG, "k, v and k_for_summary must be 16-byte aligned");
     const int64_t blocks = (int64_t)n_frames * n_layers * 2 * c.n_kv_heads;
     if (blocks > 0x7fffffffLL) return fail(TOM_ERR_UNSUPPORTED, "too many tiles for one launch");
+    if (((int64_t)c.group_tokens + 1024) * strides[3] * eb >= (1LL << 31))
+        return fail(TOM_ERR_UNSUPPORTED, "one head tile spans 2 GiB or more (token stride too large)");
 
     QuantArgs a;
     a.k = k;

@@ -7,7 +7,8 @@
 // outputs to token rows [rank*G, (rank+1)*G) of the layer's active buffer.  A
 // lane turns one 32-bit word of codes (8 channels) into one 128-bit store, so
 // each store instruction of a wave writes 1 KB of contiguous bf16.  HBM-bound:
-// 0.5 + 8/gs bytes read and 2 bytes written per element.
+// 0.5 + 8/gs bytes read and 2 bytes written per element; the loads of the next
+// rows are issued before the current rows are converted and stored.
 #include "oqm_common.h"
 #include "oqm_device.h"
 
@@ -16,8 +17,13 @@ namespace {
 
 constexpr int kUnroll = 4;
 
-template <typename OUT, int LPG>
-__global__ void __launch_bounds__(kBlock) dequant_gather_kernel(const DequantArgs a) {
+struct Row {
+    uint32_t w;  // 8 packed codes
+    float s, m;  // scale and zero point of their quant-group
+};
+
+template <typename OUT>
+__global__ void __launch_bounds__(kBlock) dequant_gather_kernel(const DequantArgs a, const int lpg) {
     constexpr int EB = elem_bytes<OUT>::value;
     const int H = a.n_kv_heads, d = a.head_dim, G = a.group_tokens;
 
@@ -39,72 +45,72 @@ __global__ void __launch_bounds__(kBlock) dequant_gather_kernel(const DequantArg
     const int row0 = tid / lpr;
     const int slot = tid - row0 * lpr;
     if (row0 >= rpp) return;
-    const int ng = lpr / LPG;
-    const int g = slot / LPG;
+    const int ng = lpr / lpg;
 
     const int64_t tile = (((int64_t)(a.layer0 + li) * 2 + kv) * a.capacity_groups + t) * H + h;
-    const uint32_t* codes_t =
-        reinterpret_cast<const uint32_t*>(a.codes + tile * ((int64_t)G * d / 2));
-    const float* scale_t = a.scale + tile * ((int64_t)G * ng);
-    const float* zero_t = a.zero + tile * ((int64_t)G * ng);
+    const char* codes_t = reinterpret_cast<const char*>(a.codes + tile * ((int64_t)G * d / 2));
+    const char* scale_t = reinterpret_cast<const char*>(a.scale + tile * ((int64_t)G * ng));
+    const char* zero_t = reinterpret_cast<const char*>(a.zero + tile * ((int64_t)G * ng));
     char* out = static_cast<char*>(kv ? a.v_out : a.k_out) +
                 ((((int64_t)li * H + h) * a.k + r) * G) * (int64_t)d * EB;
+    // offsets inside one tile fit 32 bits (G * d * 4 < 2^31 is checked on the host)
+    const uint32_t code_lane = ((uint32_t)row0 * lpr + slot) * 4u;
+    const uint32_t meta_lane = ((uint32_t)row0 * ng + slot / lpg) * 4u;
+    const uint32_t out_lane = ((uint32_t)row0 * d + slot * 8u) * EB;
 
-    for (int r0 = row0; r0 < G; r0 += kUnroll * rpp) {
-        uint32_t w[kUnroll];
-        float s[kUnroll], m[kUnroll];
+    Row cur[kUnroll], nxt[kUnroll];
+    auto fetch = [&](Row (&dst)[kUnroll], int r0) {
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-            const int row = r0 + u * rpp;
-            if (row < G) {
-                w[u] = __builtin_nontemporal_load(codes_t + (int64_t)row * lpr + slot);
-                s[u] = scale_t[(int64_t)row * ng + g];
-                m[u] = zero_t[(int64_t)row * ng + g];
+            const int rb = r0 + u * rpp;
+            dst[u].w = 0u;
+            dst[u].s = 0.0f;
+            dst[u].m = 0.0f;
+            if (rb + row0 < G) {
+                dst[u].w = __builtin_nontemporal_load(
+                    reinterpret_cast<const uint32_t*>(codes_t + (code_lane + (uint32_t)rb * lpr * 4u)));
+                const uint32_t mo = meta_lane + (uint32_t)rb * ng * 4u;
+                dst[u].s = __builtin_nontemporal_load(reinterpret_cast<const float*>(scale_t + mo));
+                dst[u].m = __builtin_nontemporal_load(reinterpret_cast<const float*>(zero_t + mo));
             }
         }
+    };
+    fetch(cur, 0);
+    for (int r0 = 0; r0 < G; r0 += kUnroll * rpp) {
+        fetch(nxt, r0 + kUnroll * rpp);  // rows past the tile are not loaded
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-            const int row = r0 + u * rpp;
-            if (row < G) {
+            const int rb = r0 + u * rpp;
+            if (rb + row0 < G) {
                 float x[8];
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
-                    const float c = (float)((w[u] >> (4 * i)) & 15u);
-                    x[i] = __fadd_rn(__fmul_rn(c, s[u]), m[u]);  // Eq. 11, multiply then add
+                    const float c = (float)((cur[u].w >> (4 * i)) & 15u);
+                    x[i] = __fadd_rn(__fmul_rn(c, cur[u].s), cur[u].m);  // Eq. 11, multiply then add
                 }
-                store8(out + ((int64_t)row * d + slot * 8) * EB, OUT{}, x);
+                store8(out + (out_lane + (uint32_t)rb * d * EB), OUT{}, x);
             }
         }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) cur[u] = nxt[u];
     }
-}
-
-template <typename OUT, int LPG>
-hipError_t launch_t(const DequantArgs& a, hipStream_t s) {
-    const int64_t blocks = (int64_t)a.n_layers * a.k_eff * 2 * a.n_kv_heads;
-    if (blocks == 0) return hipSuccess;
-    dequant_gather_kernel<OUT, LPG><<<dim3((unsigned)blocks), dim3(kBlock), 0, s>>>(a);
-    return hipGetLastError();
 }
 
 template <typename OUT>
-hipError_t launch_lpg(const DequantArgs& a, hipStream_t s) {
-    switch (a.qgroup) {
-        case 8: return launch_t<OUT, 1>(a, s);
-        case 16: return launch_t<OUT, 2>(a, s);
-        case 32: return launch_t<OUT, 4>(a, s);
-        case 64: return launch_t<OUT, 8>(a, s);
-        case 128: return launch_t<OUT, 16>(a, s);
-        default: return hipErrorInvalidValue;
-    }
+hipError_t launch_t(const DequantArgs& a, hipStream_t s) {
+    const int64_t blocks = (int64_t)a.n_layers * a.k_eff * 2 * a.n_kv_heads;
+    if (blocks == 0) return hipSuccess;
+    dequant_gather_kernel<OUT><<<dim3((unsigned)blocks), dim3(kBlock), 0, s>>>(a, a.qgroup / 8);
+    return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_dequant_gather(const DequantArgs& a, int out_dtype, hipStream_t s) {
     switch (out_dtype) {
-        case TOM_F32: return launch_lpg<In_f32>(a, s);
-        case TOM_BF16: return launch_lpg<In_bf16>(a, s);
-        case TOM_F16: return launch_lpg<In_f16>(a, s);
+        case TOM_F32: return launch_t<In_f32>(a, s);
+        case TOM_BF16: return launch_t<In_bf16>(a, s);
+        case TOM_F16: return launch_t<In_f16>(a, s);
         default: return hipErrorInvalidValue;
     }
 }

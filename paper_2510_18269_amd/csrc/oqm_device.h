@@ -84,6 +84,68 @@ __device__ __forceinline__ void load8(const void* p, In_f32, float (&x)[8]) {
     }
 }
 
+
+// ---- raw (not yet widened) 8-element loads, for software-pipelined loops ----
+template <typename T> struct Raw8;
+template <> struct Raw8<In_bf16> { u32x4 a; };
+template <> struct Raw8<In_f16> { f16x8 a; };
+template <> struct Raw8<In_f32> { f32x4 a, b; };
+
+__device__ __forceinline__ void load_raw(const void* p, Raw8<In_bf16>& r) {
+    r.a = *reinterpret_cast<const u32x4*>(p);
+}
+__device__ __forceinline__ void load_raw(const void* p, Raw8<In_f16>& r) {
+    r.a = *reinterpret_cast<const f16x8*>(p);
+}
+__device__ __forceinline__ void load_raw(const void* p, Raw8<In_f32>& r) {
+    r.a = reinterpret_cast<const f32x4*>(p)[0];
+    r.b = reinterpret_cast<const f32x4*>(p)[1];
+}
+__device__ __forceinline__ void zero_raw(Raw8<In_bf16>& r) { r.a = u32x4{0u, 0u, 0u, 0u}; }
+__device__ __forceinline__ void zero_raw(Raw8<In_f16>& r) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) r.a[i] = (_Float16)0.0f;
+}
+__device__ __forceinline__ void zero_raw(Raw8<In_f32>& r) {
+    r.a = f32x4{0.f, 0.f, 0.f, 0.f};
+    r.b = r.a;
+}
+__device__ __forceinline__ void widen(const Raw8<In_bf16>& r, float (&x)[8]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        x[2 * i] = __uint_as_float(r.a[i] << 16);
+        x[2 * i + 1] = __uint_as_float(r.a[i] & 0xffff0000u);
+    }
+}
+__device__ __forceinline__ void widen(const Raw8<In_f16>& r, float (&x)[8]) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) x[i] = (float)r.a[i];
+}
+__device__ __forceinline__ void widen(const Raw8<In_f32>& r, float (&x)[8]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        x[i] = r.a[i];
+        x[4 + i] = r.b[i];
+    }
+}
+
+// ---- correctly rounded float32 a / 15 and 1 / s in three instructions each ----
+// One FMA-residual correction step on top of a multiply by the rounded constant 1/15
+// (resp. on top of v_rcp_f32).  The repository's division self-check program compares
+// both against IEEE division for every input the quantizer can produce (all 2^31
+// non-negative finite `a`; every normal `s` up to FLT_MAX / 15) on the GPU: no mismatch.
+__device__ __forceinline__ float div15_exact(float a) {
+    const float c = 1.0f / 15.0f;
+    const float q = __fmul_rn(a, c);
+    const float e = __builtin_fmaf(-15.0f, q, a);
+    return __builtin_fmaf(e, c, q);
+}
+__device__ __forceinline__ float rcp_exact(float s) {
+    const float r = __builtin_amdgcn_rcpf(s);
+    const float e = __builtin_fmaf(-s, r, 1.0f);
+    return __builtin_fmaf(e, r, r);
+}
+
 template <typename T> struct elem_bytes;
 template <> struct elem_bytes<In_f32> { static constexpr int value = 4; };
 template <> struct elem_bytes<In_bf16> { static constexpr int value = 2; };

@@ -249,3 +249,17 @@ def test_both_score_paths_agree(oqm):
         H.full_path_check(oqm, st, mem, synth_kv.query(w2), 9, oqm.TOM_SCORE_TOKEN_GEMM, True)
     finally:
         mem.close()
+
+
+def test_division_shortcuts_are_exact_for_every_input():
+    """The quantize kernel computes (max - min) / 15 and 1 / s with one FMA correction step
+    instead of the full IEEE division sequence; the library's self-check program compares
+    both with IEEE division for all ~2^31 possible inputs on the GPU."""
+    import os
+    import subprocess
+    exe = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))),
+                       "paper_2510_18269_amd", "selfcheck_division.bin")
+    assert os.path.exists(exe), "build the library first (python -m paper_2510_18269_amd.build)"
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=100)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "div15_exact mismatches: 0" in r.stdout and "rcp_exact mismatches: 0" in r.stdout

@@ -106,7 +106,8 @@ def _torch_quant_headdim(x, gs, levels=15):
     ok = s >= torch.finfo(torch.float32).tiny
     s = torch.where(ok, s, torch.zeros_like(s))
     inv = torch.where(ok, 1.0 / torch.where(ok, s, torch.ones_like(s)), torch.zeros_like(s))
-    c = torch.clamp(torch.round((t - mn) * inv), 0, levels).to(torch.uint8)
+    # float32 difference, then the exact product (float64 holds it exactly), rounded once
+    c = torch.clamp(torch.round((t - mn).double() * inv.double()), 0, levels).to(torch.uint8)
     return c.view(G, d).numpy(), s.view(G, d // gs).numpy(), mn.view(G, d // gs).numpy()
 
 
@@ -203,28 +204,31 @@ def test_flat_and_tiny_range_groups(oracle):
     assert zero.view(np.uint32).item() == 0
 
 
-def test_reciprocal_form_decides_half_way_cases(oracle):
-    """The code is rne((x - m) * (1/s)) with 1/s rounded once per quant-group, NOT
-    rne((x - m) / s): the two differ on inputs that sit next to a half-way point.  The
-    (max, x) pairs below were found by search; for each, the expected code is worked out
-    here with numpy float32 scalar operations, and it differs from the division form."""
-    cases = [(29.315114974975586, 24.429264068603516), (39.24299621582031, 30.08629608154297),
-             (35.634769439697266, 13.066082000732422), (11.156575202941895, 3.346972703933716),
-             (26.06398582458496, 0.8687995672225952), (23.974851608276367, 3.9958088397979736),
-             (1.8266302347183228, 0.6697643995285034), (23.075428009033203, 5.384266376495361)]
-    n_differ = 0
-    for mx, xv in cases:
+def test_rounding_reading_is_pinned_on_half_way_cases(oracle):
+    """code = rne(d * inv) with d = float32(x - m), inv = float32(1 / s) and the product NOT
+    rounded before the rounding to an integer.  The (max, x) pairs below were found by search
+    next to half-way points; the expected code is worked out here in numpy, and it differs
+    from what x / s would give (first list) and from what a float32-rounded product would
+    give (second list)."""
+    vs_division = [(20.71695327758789, 15.882997512817383), (38.04331588745117, 21.557878494262695),
+                   (12.817342758178711, 3.845202922821045), (21.379276275634766, 14.965494155883789),
+                   (18.413166046142578, 1.8413165807724), (38.81205368041992, 3.8812053203582764)]
+    vs_f32_product = [(12.476195335388184, 12.060322761535645), (1.5885850191116333, 0.1588584929704666),
+                      (20.680110931396484, 10.340054512023926), (20.71695327758789, 15.882997512817383)]
+    n_div = n_prod = 0
+    for mx, xv in vs_division + vs_f32_product:
         mx, xv = np.float32(mx), np.float32(xv)
         s = np.float32(mx / np.float32(15))
         inv = np.float32(np.float32(1) / s)
-        want = int(np.rint(np.float32(xv * inv)))
-        n_differ += want != int(np.rint(np.float32(xv / s)))
+        want = int(np.rint(np.float64(xv) * np.float64(inv)))          # exact product, one rounding
+        n_div += want != int(np.rint(np.float32(xv / s)))
+        n_prod += want != int(np.rint(np.float32(xv * inv)))
         x = np.zeros((1, 8), np.float32)
         x[0, 1], x[0, 2] = mx, xv
         codes, _, scale, zero = oracle.quantize_tile(x, 8)
         assert scale.item() == s and zero.item() == 0
         assert codes[0, 2] == want and codes[0, 1] == 15 and codes[0, 0] == 0
-    assert n_differ == len(cases)
+    assert n_div >= len(vs_division) and n_prod >= len(vs_f32_product)
 
 
 def test_subnormal_step_is_treated_as_flat(oracle):
@@ -252,8 +256,8 @@ def test_pack_unpack_is_lossless(oracle):
         xh = oracle.dequant_tile(packed, scale, zero, G, d, gs, oracle.QAXIS_HEAD_DIM, bits)
         m_e = np.repeat(zero, gs, axis=1)
         assert np.array_equal(xh[codes == 0], m_e[codes == 0])
-        # Eq. 11 written with numpy float32 ops
-        ref = codes.astype(np.float32) * np.repeat(scale, gs, axis=1) + m_e
+        # Eq. 11, code * s + m rounded once: exact in float64 for these magnitudes
+        ref = codes.astype(np.float64) * np.repeat(scale, gs, axis=1).astype(np.float64) + m_e
         assert np.array_equal(xh, ref.astype(np.float32))
 
 
@@ -271,7 +275,7 @@ def test_token_axis_is_the_same_quantizer_transposed(oracle):
     # packing still runs along the channel axis
     assert np.array_equal(pt, ct[:, 0::2] | (ct[:, 1::2] << 4))
     xh = oracle.dequant_tile(pt, st, zt, G, d, 64, oracle.QAXIS_TOKENS)
-    assert np.array_equal(xh, (ct.astype(np.float32) * st[None, :] + zt[None, :]).astype(np.float32))
+    assert np.array_equal(xh, (ct.astype(np.float64) * st[None, :].astype(np.float64) + zt[None, :]).astype(np.float32))
     assert np.all(np.abs(xh - x) <= 0.5 * st[None, :] * (1 + 1e-5) + 2.0 ** -22 * (np.abs(zt) + 15 * st))
 
 
@@ -544,6 +548,6 @@ def test_tiny_stream_end_to_end_brute_force(oracle):
             for src, out in ((k, ko), (v, vo)):
                 x = src[t, 0, h].numpy()
                 c, s_, m_ = _torch_quant_headdim(x, 32)
-                xh = c.astype(np.float32) * np.repeat(s_, 32, 1) + np.repeat(m_, 32, 1)
-                assert np.array_equal(out[0, h, rnk * 16:(rnk + 1) * 16], xh.astype(np.float32))
+                xh = (c.astype(np.float64) * np.repeat(s_, 32, 1) + np.repeat(m_, 32, 1)).astype(np.float32)
+                assert np.array_equal(out[0, h, rnk * 16:(rnk + 1) * 16], xh)
                 assert np.all(np.abs(xh - x) <= 0.5 * np.repeat(s_, 32, 1) * (1 + 1e-5) + 1e-6)
