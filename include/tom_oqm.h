@@ -34,9 +34,9 @@
  *   codes  [L][2 (0 = K, 1 = V)][T_cap][H_k][G][d * bits / 8]   uint8
  *          4-bit: channel 2j in the low nibble of byte j, channel 2j+1 in the high nibble
  *          2-bit: channel 4j + u in bits [2u, 2u + 2) of byte j
- *   scale, zero
- *          qaxis HEAD_DIM: [L][2][T_cap][H_k][G][d / gs]         float32
- *          qaxis TOKENS  : [L][2][T_cap][H_k][d]                 float32
+ *   meta   (scale, zero) pairs, scale first
+ *          qaxis HEAD_DIM: [L][2][T_cap][H_k][G][d / gs][2]      float32
+ *          qaxis TOKENS  : [L][2][T_cap][H_k][d][2]              float32
  *   keys   [L][T_cap][H_k][d]                                    float32 (summary keys)
  * One (layer, K|V, frame-group, head) tile is contiguous in every array, so a
  * tile is appended with full-width stores and retrieved with full-width loads.
@@ -100,14 +100,13 @@ typedef struct {
 
 typedef struct {
     size_t codes; /* bytes of each storage array for this configuration */
-    size_t scale;
-    size_t zero;
+    size_t meta;
     size_t keys;
 } tom_oqm_sizes_t;
 
 /* ---- handle management (host only, no GPU work) ------------------------- */
 
-/* Byte sizes of the four storage arrays the caller must allocate (layout
+/* Byte sizes of the three storage arrays the caller must allocate (layout
  * above).  INVALID_ARG / UNSUPPORTED if the configuration is not usable. */
 tom_status_t tom_oqm_query_sizes(const tom_oqm_config_t* cfg, tom_oqm_sizes_t* sizes);
 
@@ -118,8 +117,8 @@ tom_status_t tom_oqm_create(const tom_oqm_config_t* cfg, tom_oqm_t** out);
 /* Binds caller-owned device arrays of at least the sizes reported by
  * tom_oqm_query_sizes.  The contents are not touched: binding arrays that
  * already hold a stream, then tom_oqm_set_num_groups, restores a checkpoint. */
-tom_status_t tom_oqm_bind(tom_oqm_t* h, void* codes_device, void* scale_device,
-                          void* zero_device, void* keys_device);
+tom_status_t tom_oqm_bind(tom_oqm_t* h, void* codes_device, void* meta_device,
+                          void* keys_device);
 
 /* Forget all stored groups (the memory itself is not cleared). */
 tom_status_t tom_oqm_reset(tom_oqm_t* h);
@@ -143,9 +142,11 @@ int32_t tom_oqm_k_from_budget(int64_t budget_tokens, int32_t group_tokens, int32
  * Quantizes n_frames frame-groups of layers [layer0, layer0 + n_layers) and
  * writes them to group slots T .. T + n_frames - 1, T = tom_oqm_num_groups(h).
  * Per quant-group: m = min, s = (max - min) / 15 in float32;
- * code = clamp(round_half_even((x - m) * (1 / s)), 0, 15), 1 / s rounded once
- * per quant-group; s below FLT_MIN (e.g. max == min) is stored as 0 with all
- * codes 0; m is stored as +0 rather than -0.  K and V use the same quantizer.
+ * code = clamp(round_half_even(d * inv), 0, 15) with d = float32(x - m),
+ * inv = float32(1 / s) computed once per quant-group, and the product d * inv
+ * not rounded before the rounding to an integer; s below FLT_MIN (e.g.
+ * max == min) is stored as 0 with all codes 0; m is stored as +0 rather than
+ * -0.  K and V use the same quantizer.
  * Also writes one summary key per (layer, frame-group, KV head): the mean over
  * the G tokens of the un-quantized keys (accumulated in float64, rounded once).
  *
@@ -226,8 +227,8 @@ tom_status_t tom_oqm_topk(const float* scores_device, int64_t score_stride, int3
  * buffer (Eq. 13; supplement "Cache reconstruction for decoding").
  * For each layer li < n_layers and rank r < k_eff, frame-group
  * t = idx[li * k + r] of K and of V is dequantized, x = float(code) * s + m
- * (float32 multiply then add, then rounded to cfg.out_dtype, ties to even),
- * into token rows [r * G, (r + 1) * G) of that layer's buffers.
+ * (one fused float32 multiply-add, then rounded to cfg.out_dtype, ties to
+ * even), into token rows [r * G, (r + 1) * G) of that layer's buffers.
  *   idx           device int32 [n_layers][k] (as written by tom_oqm_topk; it
  *                 stays on the device between the two calls)
  *   k_out, v_out  device, [n_layers][H_k][k * G][d] of cfg.out_dtype, 16-byte

@@ -79,8 +79,7 @@ tom_status_t tom_oqm_query_sizes(const tom_oqm_config_t* cfg, tom_oqm_sizes_t* s
     const Layout lay = layout_of(*cfg);
     const size_t tiles = (size_t)cfg->n_layers * 2 * (size_t)cfg->capacity_groups * cfg->n_kv_heads;
     sizes->codes = tiles * (size_t)lay.tile_code_bytes;
-    sizes->scale = tiles * (size_t)lay.tile_meta * sizeof(float);
-    sizes->zero = sizes->scale;
+    sizes->meta = tiles * (size_t)lay.tile_meta * 2 * sizeof(float);
     sizes->keys = (size_t)cfg->n_layers * cfg->capacity_groups * cfg->n_kv_heads * cfg->head_dim *
                   sizeof(float);
     return TOM_OK;
@@ -97,15 +96,14 @@ tom_status_t tom_oqm_create(const tom_oqm_config_t* cfg, tom_oqm_t** out) {
     return TOM_OK;
 }
 
-tom_status_t tom_oqm_bind(tom_oqm_t* h, void* codes, void* scale, void* zero, void* keys) {
+tom_status_t tom_oqm_bind(tom_oqm_t* h, void* codes, void* meta, void* keys) {
     if (!h) return fail(TOM_ERR_INVALID_ARG, "handle is NULL");
-    if (!codes || !scale || !zero || !keys)
-        return fail(TOM_ERR_INVALID_ARG, "codes, scale, zero and keys must all be non-NULL");
-    if (!aligned16(codes) || !aligned16(scale) || !aligned16(zero) || !aligned16(keys))
+    if (!codes || !meta || !keys)
+        return fail(TOM_ERR_INVALID_ARG, "codes, meta and keys must all be non-NULL");
+    if (!aligned16(codes) || !aligned16(meta) || !aligned16(keys))
         return fail(TOM_ERR_INVALID_ARG, "storage arrays must be 16-byte aligned");
     h->codes = static_cast<uint8_t*>(codes);
-    h->scale = static_cast<float*>(scale);
-    h->zero = static_cast<float*>(zero);
+    h->meta = static_cast<float*>(meta);
     h->keys = static_cast<float*>(keys);
     h->bound = true;
     return TOM_OK;
@@ -160,8 +158,8 @@ tom_status_t tom_oqm_quantize_append(tom_oqm_t* h, int32_t layer0, int32_t n_lay
         return fail(TOM_ERR_INVALID_ARG, "token stride %lld is smaller than head_dim", (long long)strides[3]);
     if (!aligned16(k) || !aligned16(v) || !aligned16(k_for_summary))
         return fail(TOM_ERR_INVALID_ARG, "k, v and k_for_summary must be 16-byte aligned");
-    const int64_t blocks = (int64_t)n_frames * n_layers * 2 * c.n_kv_heads;
-    if (blocks > 0x7fffffffLL) return fail(TOM_ERR_UNSUPPORTED, "too many tiles for one launch");
+    if (n_frames > 65535 || 2 * n_layers > 65535)
+        return fail(TOM_ERR_UNSUPPORTED, "at most 65535 frames and 32767 layers per call");
     if (((int64_t)c.group_tokens + 1024) * strides[3] * eb >= (1LL << 31))
         return fail(TOM_ERR_UNSUPPORTED, "one head tile spans 2 GiB or more (token stride too large)");
 
@@ -174,8 +172,7 @@ tom_status_t tom_oqm_quantize_append(tom_oqm_t* h, int32_t layer0, int32_t n_lay
     a.stride_head = strides[2];
     a.stride_token = strides[3];
     a.codes = h->codes;
-    a.scale = h->scale;
-    a.zero = h->zero;
+    a.meta = h->meta;
     a.keys = h->keys;
     a.n_kv_heads = c.n_kv_heads;
     a.head_dim = c.head_dim;
@@ -299,12 +296,11 @@ tom_status_t tom_oqm_dequant_gather(const tom_oqm_t* h, int32_t layer0, int32_t 
     if (!aligned16(k_out) || !aligned16(v_out))
         return fail(TOM_ERR_INVALID_ARG, "k_out and v_out must be 16-byte aligned");
     const tom_oqm_config_t& c = h->cfg;
-    const int64_t blocks = (int64_t)n_layers * k_eff * 2 * c.n_kv_heads;
-    if (blocks > 0x7fffffffLL) return fail(TOM_ERR_UNSUPPORTED, "too many tiles for one launch");
+    if (k_eff > 32767 || n_layers > 65535)
+        return fail(TOM_ERR_UNSUPPORTED, "at most 32767 groups and 65535 layers per call");
     DequantArgs a;
     a.codes = h->codes;
-    a.scale = h->scale;
-    a.zero = h->zero;
+    a.meta = h->meta;
     a.idx = idx;
     a.k_out = k_out;
     a.v_out = v_out;

@@ -10,8 +10,7 @@
 struct tom_oqm {
     tom_oqm_config_t cfg;
     uint8_t* codes = nullptr;
-    float* scale = nullptr;
-    float* zero = nullptr;
+    float* meta = nullptr;  // (scale, zero) pairs
     float* keys = nullptr;
     int32_t n_groups = 0;
     bool bound = false;
@@ -27,7 +26,7 @@ constexpr int kBlock = 256;  // threads per workgroup of the streaming kernels (
 // ---- element offsets of the storage arrays -------------------------------
 struct Layout {
     int64_t tile_code_bytes;  // G * d * bits / 8
-    int64_t tile_meta;        // (scale, zero) pairs per head tile
+    int64_t tile_meta;        // (scale, zero) pairs per head tile (2 floats each)
     int64_t tile_elems;       // G * d
 };
 
@@ -47,8 +46,7 @@ struct QuantArgs {
     const void* ksum;  // source of the summary key (== k unless the caller gave another)
     int64_t stride_frame, stride_layer, stride_head, stride_token;  // elements
     uint8_t* codes;
-    float* scale;
-    float* zero;
+    float* meta;  // [..][G][d/gs][2]: (scale, zero) pairs
     float* keys;
     int32_t n_kv_heads, head_dim, group_tokens, qgroup, capacity_groups;
     int32_t layer0, n_layers, n_frames, first_group;
@@ -56,8 +54,7 @@ struct QuantArgs {
 
 struct DequantArgs {
     const uint8_t* codes;
-    const float* scale;
-    const float* zero;
+    const float* meta;
     const int32_t* idx;  // [n_layers][k]
     void* k_out;
     void* v_out;

@@ -165,7 +165,14 @@ __device__ __forceinline__ void store8(void* p, In_bf16, const float (&x)[8]) {
 __device__ __forceinline__ void store8(void* p, In_f16, const float (&x)[8]) {
     f16x8 h;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) h[i] = (_Float16)x[i];  // v_cvt_f16_f32, ties to even
+    for (int i = 0; i < 8; ++i) {
+        // The value must be rounded to float32 first and to binary16 second; the empty asm
+        // keeps the compiler from folding a producing FMA and this narrowing into one
+        // mixed-precision instruction that rounds only once.
+        float v = x[i];
+        asm volatile("" : "+v"(v));
+        h[i] = (_Float16)v;  // v_cvt_f16_f32, ties to even
+    }
     __builtin_nontemporal_store(h, reinterpret_cast<f16x8*>(p));
 }
 

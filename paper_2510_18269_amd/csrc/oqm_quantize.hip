@@ -4,31 +4,37 @@
 // tokens of the group) in the same pass over K.
 //
 // Work decomposition.  One workgroup of 256 threads owns one
-// (frame, layer, K|V, head) tile of G x d elements.  A lane owns 8 consecutive
-// channels of one token row: one 128-bit load in, one 32-bit word of packed
-// nibbles out, so every load and store instruction of a wave covers one
-// contiguous span (1 KB in, 256 B out).  A quant-group of gs channels lives in
-// gs/8 adjacent lanes; its min and max are all-reduced with DPP lane swaps, no
-// LDS.  The kernel is HBM-bound: per element it reads 2 B (bf16) and writes
-// 0.5 B of codes + 8/gs B of scale/zero, so the instruction count per element
-// is kept low (about 7 vector instructions) and the next rows are already in
-// flight while the current ones are quantized.
+// (frame, layer, K|V, head) tile of G x d elements; the 3-D grid is
+// (head, 2*layer + K|V, frame) so no index division is needed.  A lane owns 8
+// consecutive channels of one token row: one 128-bit load in, one 32-bit word
+// of packed nibbles out, so every load and store instruction of a wave covers
+// one contiguous span (1 KB in, 256 B out).  A quant-group of gs channels
+// lives in gs/8 adjacent lanes; its min and max are all-reduced with DPP lane
+// swaps; the first lane of the group stores its (scale, zero) pair (8 bytes).
+//
+// The kernel moves 2.64 B per element (bf16 in, gs 64).  At HBM speed that leaves
+// room for only about a dozen instructions per element on the plain fp32 vector
+// pipe (64 lanes per CU and clock), so the arithmetic is arranged to need few:
+//   widen 1, min/max 1, subtract 1, fused scale-and-round 1, pack 1, plus two
+//   float64 instructions per element of K for the summary key,
+// and the register footprint is kept small: measured, more resident waves help
+// this kernel more than deeper software prefetch does.
 #include "oqm_common.h"
 #include "oqm_device.h"
 
 namespace oqm {
 namespace {
 
-constexpr int kUnroll = 4;  // token rows per lane and loop trip; twice that many loads in flight
+constexpr int kUnroll = 2;  // token rows per lane and loop trip
 
-// Packs the 4-bit codes of 8 values t[i] in [0, 15] (already divided by the step).
-// Adding 2^23 rounds t to the nearest integer, ties to even, and leaves that integer in
-// the low mantissa bits: bits(t + 2^23) = 0x4B000000 | code.
+// t[i] = fma(x_i - m, 1/s, 2^23): the exact product is rounded once, to an integer,
+// ties to even, and that integer sits in the low mantissa bits:
+// bits(t) = 0x4B000000 | code.  Packs 8 codes, even channel in the low nibble.
 __device__ __forceinline__ uint32_t pack8(const float (&t)[8]) {
     uint32_t m[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) m[i] = __float_as_uint(__fadd_rn(t[i], 8388608.0f));
-    // byte 0 of (m[2j+1] << 4 | m[2j]) is the packed byte j; bits 8..23 of it are zero
+    for (int i = 0; i < 8; ++i) m[i] = __float_as_uint(t[i]);
+    // byte 0 of (m[2j+1] << 4 | m[2j]) is packed byte j; bits 8..23 of it are zero
     const uint32_t b01 = (m[1] << 4) | m[0];
     const uint32_t b23 = (m[3] << 4) | m[2];
     const uint32_t b45 = (m[5] << 4) | m[4];
@@ -43,14 +49,10 @@ __global__ void __launch_bounds__(kBlock) quantize_append_kernel(const QuantArgs
     constexpr int EB = elem_bytes<IN>::value;
     const int H = a.n_kv_heads, d = a.head_dim, G = a.group_tokens;
 
-    // blockIdx -> (frame f, layer li, kv, head h), head fastest
-    int b = blockIdx.x;
-    const int h = b % H;
-    b /= H;
-    const int kv = b & 1;
-    b >>= 1;
-    const int li = b % a.n_layers;
-    const int f = b / a.n_layers;
+    const int h = blockIdx.x;
+    const int kv = blockIdx.y & 1;
+    const int li = blockIdx.y >> 1;
+    const int f = blockIdx.z;
     const int l = a.layer0 + li;
     const int64_t t = (int64_t)a.first_group + f;
 
@@ -61,6 +63,7 @@ __global__ void __launch_bounds__(kBlock) quantize_append_kernel(const QuantArgs
     const int slot = tid - row0 * lpr;
     const bool active = row0 < rpp;
     const int ng = lpr / LPG;       // quant-groups per token row
+    const int wave_row0 = __builtin_amdgcn_readfirstlane(row0);  // lowest row of this wave
 
     // Tile bases are uniform per workgroup; per-lane offsets inside a tile fit 32 bits
     // (checked on the host), which keeps the address arithmetic per row to one add.
@@ -68,42 +71,38 @@ __global__ void __launch_bounds__(kBlock) quantize_append_kernel(const QuantArgs
     const char* src = static_cast<const char*>(kv ? a.v : a.k) + in_off * EB;
     const int64_t tile = (((int64_t)l * 2 + kv) * a.capacity_groups + t) * H + h;
     char* codes_t = reinterpret_cast<char*>(a.codes + tile * ((int64_t)G * d / 2));
-    char* scale_t = reinterpret_cast<char*>(a.scale + tile * ((int64_t)G * ng));
-    char* zero_t = reinterpret_cast<char*>(a.zero + tile * ((int64_t)G * ng));
+    f32x2* meta_t = reinterpret_cast<f32x2*>(a.meta) + tile * ((int64_t)G * ng);
     const uint32_t in_row_bytes = (uint32_t)a.stride_token * EB;
     const uint32_t in_lane = (uint32_t)row0 * in_row_bytes + (uint32_t)slot * 8u * EB;
     const uint32_t code_lane = ((uint32_t)row0 * lpr + slot) * 4u;
-    const uint32_t meta_lane = ((uint32_t)row0 * ng + slot / LPG) * 4u;
+    const int meta_lane = row0 * ng + slot / LPG;
     const bool meta_writer = (slot & (LPG - 1)) == 0;
+
+    __shared__ double shared_buf[kBlock * 8];  // 16 KB, key reduction
 
     const bool do_sum = (kv == 0);
     double acc[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[i] = 0.0;
 
-    Raw8<IN> cur[kUnroll], nxt[kUnroll];
     auto fetch = [&](Raw8<IN> (&dst)[kUnroll], int r0) {
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-            const int row = r0 + u * rpp + row0;
-            if (active && row < G)
-                load_raw(src + (in_lane + (uint32_t)(r0 + u * rpp) * in_row_bytes), dst[u]);
-            else
-                zero_raw(dst[u]);
+            const int rb = r0 + u * rpp;
+            if (active && rb + row0 < G)
+                load_raw(src + (in_lane + (uint32_t)rb * in_row_bytes), dst[u]);
         }
     };
-    fetch(cur, 0);
-
-    for (int r0 = 0; r0 < G; r0 += kUnroll * rpp) {
-        fetch(nxt, r0 + kUnroll * rpp);  // rows past the tile are not loaded (zeros)
+    auto process = [&](const Raw8<IN> (&buf)[kUnroll], int r0) {
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
-            const int rbase = r0 + u * rpp;
-            const bool ok = active && rbase + row0 < G;
+            const int rb = r0 + u * rpp;
+            if (rb + wave_row0 >= G) break;  // nothing left for this wave (uniform)
+            const bool ok = active && rb + row0 < G;
             float x[8];
-            widen(cur[u], x);
-            // Eq. 9: m = min, s = (max - min) / 15 over the quant-group.  Every lane takes
-            // part in the lane swaps (idle lanes carry zeros) so the DPP reads are defined.
+            widen(buf[u], x);  // lanes past the tile compute on stale rows; their results are dropped
+            // Eq. 9: m = min, s = (max - min) / 15 over the quant-group.  All lanes of a
+            // quant-group share one row, so a live lane only ever swaps with live lanes.
             float mn = x[0], mx = x[0];
 #pragma unroll
             for (int i = 1; i < 8; ++i) {
@@ -122,24 +121,31 @@ __global__ void __launch_bounds__(kBlock) quantize_append_kernel(const QuantArgs
             }
             float tq[8];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) tq[i] = __fmul_rn(__fsub_rn(x[i], mn), inv);  // in [0, 15]
-            const uint32_t packed = pack8(tq);  // even channel = low nibble
+            for (int i = 0; i < 8; ++i)
+                tq[i] = __builtin_fmaf(__fsub_rn(x[i], mn), inv, 8388608.0f);
+            const uint32_t packed = pack8(tq);
             if (ok) {
-                __builtin_nontemporal_store(
-                    packed, reinterpret_cast<uint32_t*>(codes_t + (code_lane + (uint32_t)rbase * lpr * 4u)));
+                *reinterpret_cast<uint32_t*>(codes_t + (code_lane + (uint32_t)rb * lpr * 4u)) = packed;
                 if (meta_writer) {
-                    const uint32_t mo = meta_lane + (uint32_t)rbase * ng * 4u;
-                    __builtin_nontemporal_store(s, reinterpret_cast<float*>(scale_t + mo));
-                    __builtin_nontemporal_store(mn, reinterpret_cast<float*>(zero_t + mo));
+                    const f32x2 sm = {s, mn};
+                    meta_t[meta_lane + rb * ng] = sm;
+                }
+                if (!SEPARATE_SUMMARY && do_sum) {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) acc[i] += (double)x[i];
                 }
             }
-            if (!SEPARATE_SUMMARY && do_sum) {
-#pragma unroll
-                for (int i = 0; i < 8; ++i) acc[i] += (double)x[i];  // idle lanes add 0
-            }
         }
+    };
+
+    Raw8<IN> buf[kUnroll];
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) cur[u] = nxt[u];
+    for (int u = 0; u < kUnroll; ++u) zero_raw(buf[u]);  // defined contents for rows never loaded
+    const int step = kUnroll * rpp;
+    for (int r0 = 0; r0 < G; r0 += step) {
+        if (r0 + wave_row0 >= G) break;  // nothing left for this wave (uniform)
+        fetch(buf, r0);
+        process(buf, r0);
     }
 
     if (!do_sum) return;  // uniform per workgroup
@@ -157,28 +163,27 @@ __global__ void __launch_bounds__(kBlock) quantize_append_kernel(const QuantArgs
     }
 
     // Summary key: column sums over the rpp row slots of the workgroup, in float64.
-    __shared__ double red[kBlock * 8];
     if (active) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) red[row0 * d + slot * 8 + i] = acc[i];
+        for (int i = 0; i < 8; ++i) shared_buf[row0 * d + slot * 8 + i] = acc[i];
     }
     __syncthreads();
     float* key = a.keys + (((int64_t)l * a.capacity_groups + t) * H + h) * d;
     for (int c = tid; c < d; c += kBlock) {
         double sum = 0.0;
-        for (int r = 0; r < rpp; ++r) sum += red[r * d + c];
+        for (int r = 0; r < rpp; ++r) sum += shared_buf[r * d + c];
         key[c] = (float)(sum / (double)G);
     }
 }
 
 template <typename IN, int LPG>
 hipError_t launch_t(const QuantArgs& a, hipStream_t s) {
-    const int64_t blocks = (int64_t)a.n_frames * a.n_layers * 2 * a.n_kv_heads;
-    if (blocks == 0) return hipSuccess;
+    if (a.n_frames == 0 || a.n_layers == 0) return hipSuccess;
+    const dim3 grid(a.n_kv_heads, 2 * a.n_layers, a.n_frames);
     if (a.ksum != a.k)
-        quantize_append_kernel<IN, LPG, true><<<dim3((unsigned)blocks), dim3(kBlock), 0, s>>>(a);
+        quantize_append_kernel<IN, LPG, true><<<grid, dim3(kBlock), 0, s>>>(a);
     else
-        quantize_append_kernel<IN, LPG, false><<<dim3((unsigned)blocks), dim3(kBlock), 0, s>>>(a);
+        quantize_append_kernel<IN, LPG, false><<<grid, dim3(kBlock), 0, s>>>(a);
     return hipGetLastError();
 }
 

@@ -46,7 +46,7 @@ class tom_oqm_config_t(C.Structure):
 
 
 class tom_oqm_sizes_t(C.Structure):
-    _fields_ = [(n, C.c_size_t) for n in ("codes", "scale", "zero", "keys")]
+    _fields_ = [(n, C.c_size_t) for n in ("codes", "meta", "keys")]
 
 
 def _load():
@@ -59,7 +59,7 @@ def _load():
     cfgp = C.POINTER(tom_oqm_config_t)
     L.tom_oqm_query_sizes.argtypes = [cfgp, C.POINTER(tom_oqm_sizes_t)]
     L.tom_oqm_create.argtypes = [cfgp, C.POINTER(vp)]
-    L.tom_oqm_bind.argtypes = [vp, vp, vp, vp, vp]
+    L.tom_oqm_bind.argtypes = [vp, vp, vp, vp]
     L.tom_oqm_reset.argtypes = [vp]
     L.tom_oqm_num_groups.argtypes = [vp]
     L.tom_oqm_set_num_groups.argtypes = [vp, i32]
@@ -128,8 +128,8 @@ def tom_oqm_create(cfg: tom_oqm_config_t) -> int:
     return h.value
 
 
-def tom_oqm_bind(h: int, codes, scale, zero, keys) -> None:
-    _check(lib.tom_oqm_bind(h, _ptr(codes), _ptr(scale), _ptr(zero), _ptr(keys)))
+def tom_oqm_bind(h: int, codes, meta, keys) -> None:
+    _check(lib.tom_oqm_bind(h, _ptr(codes), _ptr(meta), _ptr(keys)))
 
 
 def tom_oqm_reset(h: int) -> None:
@@ -217,8 +217,7 @@ class Memory:
     cfg: tom_oqm_config_t
     handle: int
     codes: torch.Tensor
-    scale: torch.Tensor
-    zero: torch.Tensor
+    meta: torch.Tensor     # float32 (scale, zero) pairs
     keys: torch.Tensor
 
     @staticmethod
@@ -226,11 +225,10 @@ class Memory:
         sizes = tom_oqm_query_sizes(cfg)
         h = tom_oqm_create(cfg)
         codes = torch.empty(sizes.codes, dtype=torch.uint8, device=device)
-        scale = torch.empty(sizes.scale // 4, dtype=torch.float32, device=device)
-        zero = torch.empty(sizes.zero // 4, dtype=torch.float32, device=device)
+        meta = torch.empty(sizes.meta // 4, dtype=torch.float32, device=device)
         keys = torch.empty(sizes.keys // 4, dtype=torch.float32, device=device)
-        tom_oqm_bind(h, codes, scale, zero, keys)
-        return Memory(cfg, h, codes, scale, zero, keys)
+        tom_oqm_bind(h, codes, meta, keys)
+        return Memory(cfg, h, codes, meta, keys)
 
     @property
     def n_groups(self) -> int:

@@ -69,8 +69,9 @@ def compare_storage(st, mem, lo=0, hi=None):
     hi = st.n_groups if hi is None else hi
     assert mem.n_groups == st.n_groups
     oc, os_, oz, ok = storage_views(cfg, st.codes, st.scale, st.zero, st.keys)
-    gc, gs_, gz, gk = storage_views(cfg, mem.codes.cpu().numpy(), mem.scale.cpu().numpy(),
-                                    mem.zero.cpu().numpy(), mem.keys.cpu().numpy())
+    meta = mem.meta.cpu().numpy().reshape(-1, 2)         # (scale, zero) pairs
+    gc, gs_, gz, gk = storage_views(cfg, mem.codes.cpu().numpy(), np.ascontiguousarray(meta[:, 0]),
+                                    np.ascontiguousarray(meta[:, 1]), mem.keys.cpu().numpy())
     sl = slice(lo, hi)
     _same(gc[:, :, sl], oc[:, :, sl], "packed codes")
     _same(gs_[:, :, sl].view(np.uint32), os_[:, :, sl].view(np.uint32), "scale")

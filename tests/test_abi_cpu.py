@@ -40,7 +40,7 @@ def test_sizes_follow_the_documented_layout(oqm):
     s = oqm.tom_oqm_query_sizes(cfg)
     tiles = 28 * 2 * 1024 * 4
     assert s.codes == tiles * 196 * 128 // 2
-    assert s.scale == s.zero == tiles * 196 * 2 * 4
+    assert s.meta == tiles * 196 * 2 * 2 * 4
     assert s.keys == 28 * 1024 * 4 * 128 * 4
 
 
@@ -67,9 +67,9 @@ def test_host_side_validation_before_any_launch(oqm):
             oqm.tom_oqm_quantize_append(h, 0, 2, 1, fake, fake, None, (1, 1, 1, 1))
         assert e.value.status == oqm.TOM_ERR_NOT_BOUND
         with pytest.raises(oqm.TomError) as e:
-            oqm.tom_oqm_bind(h, fake, fake + 4, fake, fake)     # misaligned
+            oqm.tom_oqm_bind(h, fake, fake + 4, fake)           # misaligned
         assert e.value.status == oqm.TOM_ERR_INVALID_ARG
-        oqm.tom_oqm_bind(h, fake, fake, fake, fake)
+        oqm.tom_oqm_bind(h, fake, fake, fake)
         assert oqm.tom_oqm_num_groups(h) == 0
         st = (2 * 2 * 16 * 64, 2 * 16 * 64, 16 * 64, 64)
         with pytest.raises(oqm.TomError) as e:           # over capacity: nothing is evicted
