@@ -46,6 +46,21 @@ def bytes_topk(w, T, k_eff):
     return w.n_layers * T * 4 + w.n_layers * k_eff * 4
 
 
+def measured_traffic(kernel, workload):
+    """HBM bytes per launch (read + written) of `kernel`, from the committed rocprofv3
+    FETCH_SIZE / WRITE_SIZE summary of this same command, or None if there is none."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_bench_{workload.lower()}.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                p = line.split()
+                if len(p) == 5 and p[0] == "traffic" and p[1] == kernel and p[2] == workload:
+                    return int(p[3]) + int(p[4])
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(w, batches_cpu, q_cpu, threads):
     """The oracle, as it stands, on a bounded sample of the same workload: the given append
     batches (all layers) and one retrieval over what they stored.  Threads split layers."""
@@ -112,7 +127,7 @@ def main():
     ap.add_argument("--workload", default="C3", choices=["C2", "C3", "C4", "C5"])
     ap.add_argument("--frames-per-append", type=int, default=0, help="override the workload's batch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-batches", type=int, default=4)
+    ap.add_argument("--cpu-sample-batches", type=int, default=12)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the path has no collectives); "
@@ -185,6 +200,21 @@ def main():
         if ev:
             ev[4].record()
 
+    # reference: a plain device-to-device copy of known size (1 GiB read + 1 GiB written),
+    # untimed part of the run; also the calibration kernel for the HBM byte counters
+    copy_src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+    copy_dst = torch.empty_like(copy_src)
+    cev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    for _ in range(2):
+        copy_dst.copy_(copy_src)
+    cev[0].record()
+    for _ in range(5):
+        copy_dst.copy_(copy_src)
+    cev[1].record()
+    torch.cuda.synchronize()
+    copy_gbps = 5 * 2 * copy_src.numel() * 4 / (cev[0].elapsed_time(cev[1]) * 1e-3) / 1e9
+    del copy_src, copy_dst
+
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -224,6 +254,7 @@ def main():
             "input_batches_rotated": n_batches,
         },
         "pct_of_hbm_peak": round(100 * gbps(total_bytes, ms_step) / HBM_PEAK_GBPS, 2),
+        "copy_GBps": round(copy_gbps, 1),
         "bytes_per_step": total_bytes,
         "append": {"ms": round(ms_append, 4), "GBps": round(gbps(b_app, ms_append), 1),
                    "pct_of_peak": round(100 * gbps(b_app, ms_append) / HBM_PEAK_GBPS, 2),
@@ -235,18 +266,20 @@ def main():
         "retrieval_ms_per_query": round(ms_score + ms_topk + ms_gather, 4),
         "roofline": {"bound": "hbm", "kernel": "dequant_gather_kernel",
                      "achieved": round(gbps(b_gat, ms_gather), 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(gbps(b_gat, ms_gather) / HBM_PEAK_GBPS, 4), "traffic": None},
+                     "frac": round(gbps(b_gat, ms_gather) / HBM_PEAK_GBPS, 4),
+                     "traffic": measured_traffic("dequant_gather_kernel", w.name),
+                     "algorithmic_bytes": b_gat, "avg_launch_us": round(ms_gather * 1e3, 2)},
         "roofline_append": {"bound": "hbm", "kernel": "quantize_append_kernel",
                             "achieved": round(gbps(b_app, ms_append), 1), "peak": HBM_PEAK_GBPS,
                             "unit": "GB/s", "frac": round(gbps(b_app, ms_append) / HBM_PEAK_GBPS, 4),
-                            "traffic": None},
+                            "traffic": measured_traffic("quantize_append_kernel", w.name),
+                            "algorithmic_bytes": b_app, "avg_launch_us": round(ms_append * 1e3, 2)},
     }
 
     if not args.no_cpu_baseline:
-        nb = max(1, min(args.cpu_sample_batches, n_batches))
-        if fpa == 1:
-            nb = min(n_batches, 16)
-        sample = [(k.cpu(), v.cpu()) for k, v in batches[:nb]]
+        nb = max(1, args.cpu_sample_batches if fpa > 1 else 64)
+        host = [(k.cpu(), v.cpu()) for k, v in batches[:min(nb, n_batches)]]
+        sample = [host[i % len(host)] for i in range(nb)]      # cycle the resident batches
         threads = min(16, os.cpu_count() or 1)
         out["cpu_baseline"] = cpu_baseline(w, sample, queries[0].cpu(), threads)
         out["cpu_baseline"]["value"] = round(out["cpu_baseline"]["value"], 3)
