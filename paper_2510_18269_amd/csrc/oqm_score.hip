@@ -141,15 +141,38 @@ __global__ void __launch_bounds__(kBlock) score_mean_query_kernel(const ScoreArg
 // 16*g + j holds D[4*v + g][j] in accumulator register v.
 constexpr int kGemmN = 64;
 constexpr int kGemmM = 64;
-constexpr int kGemmK = 32;
+#ifndef OQM_GEMM_K
+#define OQM_GEMM_K 32
+#endif
+constexpr int kGemmK = OQM_GEMM_K;
 constexpr int kLdA = kGemmK + 4;  // doubles; 2-way LDS bank conflict at most (the minimum for b64)
 constexpr int kLdB = kGemmK + 4;  // floats; conflict-free fragment reads
 
 __device__ __forceinline__ int mfma_d_row(int lane, int v) { return 4 * v + (lane >> 4); }
 
+// One staged chunk: kGemmK/4 MFMA steps for MT row tiles of 16 tokens against the 16 groups
+// of this wave.  No branches inside, so the LDS reads of a step are issued together.
+template <int MT>
+__device__ __forceinline__ void mma_chunk(const double* __restrict__ As, const float* __restrict__ Bs,
+                                          f64x4 (&acc)[kGemmM / 16], double& nk2c, int wave, int fi,
+                                          int kk) {
+#pragma unroll
+    for (int ks = 0; ks < kGemmK / 4; ++ks) {
+        const double bv = (double)Bs[(wave * 16 + fi) * kLdB + ks * 4 + kk];
+        double av[MT];
+#pragma unroll
+        for (int m = 0; m < MT; ++m) av[m] = As[(m * 16 + fi) * kLdA + ks * 4 + kk];
+        nk2c = fma(bv, bv, nk2c);
+#pragma unroll
+        for (int m = 0; m < MT; ++m)
+            acc[m] = __builtin_amdgcn_mfma_f64_16x16x4f64(av[m], bv, acc[m], 0, 0, 0);
+    }
+}
+
 __global__ void __launch_bounds__(kBlock) score_token_gemm_kernel(const ScoreArgs a) {
-    __shared__ double As[kGemmM * kLdA];
-    __shared__ float Bs[kGemmN * kLdB];
+    // two LDS stages: chunk c is multiplied while chunk c+1 travels global -> registers -> LDS
+    __shared__ double As[2][kGemmM * kLdA];
+    __shared__ float Bs[2][kGemmN * kLdB];
     const int li = blockIdx.y;
     const int n0 = blockIdx.x * kGemmN;
     const int HD = a.n_kv_heads * a.head_dim;
@@ -158,6 +181,15 @@ __global__ void __launch_bounds__(kBlock) score_token_gemm_kernel(const ScoreArg
     const int fi = lane & 15, kk = lane >> 4;
     const float* keys = a.keys + ((int64_t)(a.layer0 + li) * a.capacity_groups) * HD;
     const double* qtok = a.ws_qtok + (int64_t)li * Tq * HD;
+    const int n_chunks = (HD + kGemmK - 1) / kGemmK;
+
+    // staging roles: A = 64 token rows x kGemmK doubles, 16 B per lane; B = 64 groups x kGemmK
+    // floats, 16 B per lane
+    constexpr int kALanes = kGemmK / 2, kBLanes = kGemmK / 4;  // lanes per staged row
+    constexpr int kAPass = kBlock / kALanes, kBPass = kBlock / kBLanes;  // rows per pass
+    constexpr int kARows = kGemmM / kAPass, kBRows = kGemmN / kBPass;    // rows per thread
+    const int a_row = tid / kALanes, a_col = (tid % kALanes) * 2;
+    const int b_row = tid / kBLanes, b_col = (tid % kBLanes) * 4;
 
     double colsum = 0.0, nk2 = 0.0;
     for (int m0 = 0; m0 < Tq; m0 += kGemmM) {
@@ -166,44 +198,63 @@ __global__ void __launch_bounds__(kBlock) score_token_gemm_kernel(const ScoreArg
         f64x4 acc[kGemmM / 16];
 #pragma unroll
         for (int m = 0; m < kGemmM / 16; ++m) acc[m] = f64x4{0.0, 0.0, 0.0, 0.0};
+        double nk2c = 0.0;  // |key|^2 share of this lane, recomputed per row block
 
-        for (int k0 = 0; k0 < HD; k0 += kGemmK) {
-            __syncthreads();  // previous chunk fully consumed
-            // stage A: 64 token rows x 32 doubles, 16 lanes x 16 B per row
-            for (int rr = tid >> 4; rr < kGemmM; rr += kBlock / 16) {
-                const int c = (tid & 15) * 2;
-                double v0 = 0.0, v1 = 0.0;
-                if (rr < rows && k0 + c < HD) {
-                    const double* p = qtok + (int64_t)(m0 + rr) * HD + k0 + c;
-                    v0 = p[0];
-                    v1 = p[1];
-                }
-                As[rr * kLdA + c] = v0;
-                As[rr * kLdA + c + 1] = v1;
-            }
-            // stage B: 64 groups x 32 floats, 8 lanes x 16 B per row
-            for (int rr = tid >> 3; rr < kGemmN; rr += kBlock / 8) {
-                const int c = (tid & 7) * 4;
-                f32x4 v = {0.0f, 0.0f, 0.0f, 0.0f};
-                if (n0 + rr < T && k0 + c < HD)
-                    v = *reinterpret_cast<const f32x4*>(keys + (int64_t)(n0 + rr) * HD + k0 + c);
+        double ra[kARows][2];
+        f32x4 rb[kBRows];
+        auto load_chunk = [&](int c) {
+            const int k0 = c * kGemmK;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) Bs[rr * kLdB + c + i] = v[i];
+            for (int i = 0; i < kARows; ++i) {
+                const int rr = a_row + i * kAPass;
+                ra[i][0] = 0.0;
+                ra[i][1] = 0.0;
+                if (rr < rows && k0 + a_col < HD) {
+                    const double* p = qtok + (int64_t)(m0 + rr) * HD + k0 + a_col;
+                    ra[i][0] = p[0];
+                    ra[i][1] = p[1];
+                }
             }
+#pragma unroll
+            for (int i = 0; i < kBRows; ++i) {
+                const int rr = b_row + i * kBPass;
+                rb[i] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+                if (n0 + rr < T && k0 + b_col < HD)
+                    rb[i] = *reinterpret_cast<const f32x4*>(keys + (int64_t)(n0 + rr) * HD + k0 + b_col);
+            }
+        };
+        auto store_chunk = [&](int stage) {
+#pragma unroll
+            for (int i = 0; i < kARows; ++i) {
+                const int rr = a_row + i * kAPass;
+                As[stage][rr * kLdA + a_col] = ra[i][0];
+                As[stage][rr * kLdA + a_col + 1] = ra[i][1];
+            }
+#pragma unroll
+            for (int i = 0; i < kBRows; ++i) {
+                const int rr = b_row + i * kBPass;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) Bs[stage][rr * kLdB + b_col + j] = rb[i][j];
+            }
+        };
+
+        __syncthreads();  // the previous row block no longer reads LDS
+        load_chunk(0);
+        store_chunk(0);
+        __syncthreads();
+        for (int c = 0; c < n_chunks; ++c) {
+            const int stage = c & 1;
+            if (c + 1 < n_chunks) load_chunk(c + 1);  // in flight during the MFMAs below
+            switch (mt) {  // uniform; straight-line MFMA code per row-tile count
+                case 1: mma_chunk<1>(As[stage], Bs[stage], acc, nk2c, wave, fi, kk); break;
+                case 2: mma_chunk<2>(As[stage], Bs[stage], acc, nk2c, wave, fi, kk); break;
+                case 3: mma_chunk<3>(As[stage], Bs[stage], acc, nk2c, wave, fi, kk); break;
+                default: mma_chunk<4>(As[stage], Bs[stage], acc, nk2c, wave, fi, kk); break;
+            }
+            if (c + 1 < n_chunks) store_chunk(stage ^ 1);  // that stage was consumed before the last barrier
             __syncthreads();
-#pragma unroll
-            for (int ks = 0; ks < kGemmK / 4; ++ks) {
-                const double bv = (double)Bs[(wave * 16 + fi) * kLdB + ks * 4 + kk];
-                if (m0 == 0) nk2 = fma(bv, bv, nk2);
-#pragma unroll
-                for (int m = 0; m < kGemmM / 16; ++m) {
-                    if (m < mt) {
-                        const double av = As[(m * 16 + fi) * kLdA + ks * 4 + kk];
-                        acc[m] = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc[m], 0, 0, 0);
-                    }
-                }
-            }
         }
+        if (m0 == 0) nk2 = nk2c;
         const int t = n0 + wave * 16 + fi;
 #pragma unroll
         for (int m = 0; m < kGemmM / 16; ++m) {
