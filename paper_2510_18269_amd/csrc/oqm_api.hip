@@ -296,8 +296,8 @@ tom_status_t tom_oqm_dequant_gather(const tom_oqm_t* h, int32_t layer0, int32_t 
     if (!aligned16(k_out) || !aligned16(v_out))
         return fail(TOM_ERR_INVALID_ARG, "k_out and v_out must be 16-byte aligned");
     const tom_oqm_config_t& c = h->cfg;
-    if (k_eff > 32767 || n_layers > 65535)
-        return fail(TOM_ERR_UNSUPPORTED, "at most 32767 groups and 65535 layers per call");
+    if (2 * c.n_kv_heads > 65535 || n_layers > 65535)
+        return fail(TOM_ERR_UNSUPPORTED, "at most 32767 KV heads and 65535 layers per call");
     DequantArgs a;
     a.codes = h->codes;
     a.meta = h->meta;

@@ -1,8 +1,9 @@
 // Reconstruction of the selected frame-groups into the bounded active KV buffer
 // (paper Sec. 3.4, Eq. 11 and Eq. 13; supplement "Cache reconstruction for decoding").
 //
-// Grid (head, 2*rank + K|V, layer): one workgroup of 256 threads owns one head
-// tile of one selected group.  It reads the group index from device memory (the
+// Grid (rank, 2*head + K|V, layer): one workgroup of 256 threads owns one head
+// tile of one selected group; consecutive workgroups write consecutive row blocks
+// of the active buffer.  It reads the group index from device memory (the
 // index array never visits the host), streams the tile's packed nibbles and
 // (scale, zero) pairs, and writes G x d outputs to token rows
 // [rank*G, (rank+1)*G) of the layer's active buffer.  A lane turns one 32-bit
@@ -15,15 +16,15 @@
 namespace oqm {
 namespace {
 
-constexpr int kUnroll = 7;  // rows per lane whose loads are issued before any is converted
-
-template <typename OUT>
+// kUnroll: rows per lane whose loads are issued before any is converted; the host picks it
+// so that a whole tile is covered in one trip when it fits (13 trips of 16 rows for 196 x 128).
+template <typename OUT, int kUnroll>
 __global__ void __launch_bounds__(kBlock) dequant_gather_kernel(const DequantArgs a, const int lpg) {
     constexpr int EB = elem_bytes<OUT>::value;
     const int H = a.n_kv_heads, d = a.head_dim, G = a.group_tokens;
-    const int h = blockIdx.x;
+    const int r = blockIdx.x;
     const int kv = blockIdx.y & 1;
-    const int r = blockIdx.y >> 1;
+    const int h = blockIdx.y >> 1;
     const int li = blockIdx.z;
 
     const int t = a.idx[(int64_t)li * a.k + r];
@@ -79,8 +80,16 @@ __global__ void __launch_bounds__(kBlock) dequant_gather_kernel(const DequantArg
 template <typename OUT>
 hipError_t launch_t(const DequantArgs& a, hipStream_t s) {
     if (a.n_layers == 0 || a.k_eff == 0) return hipSuccess;
-    dequant_gather_kernel<OUT><<<dim3(a.n_kv_heads, 2 * a.k_eff, a.n_layers), dim3(kBlock), 0, s>>>(
-        a, a.qgroup / 8);
+    const dim3 grid(a.k_eff, 2 * a.n_kv_heads, a.n_layers), block(kBlock);
+    const int rpp = kBlock / (a.head_dim / 8);
+    const int trips = (a.group_tokens + rpp - 1) / rpp;  // row passes per tile
+    const int lpg = a.qgroup / 8;
+    if (trips <= 4)
+        dequant_gather_kernel<OUT, 4><<<grid, block, 0, s>>>(a, lpg);
+    else if (trips <= 8 || trips > 13)
+        dequant_gather_kernel<OUT, 8><<<grid, block, 0, s>>>(a, lpg);
+    else
+        dequant_gather_kernel<OUT, 13><<<grid, block, 0, s>>>(a, lpg);
     return hipGetLastError();
 }
 

@@ -43,12 +43,25 @@ __global__ void __launch_bounds__(kBlock) query_fold_kernel(const ScoreArgs a, c
             double qt[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i) qt[i] = 0.0;
-            for (int g = 0; g < r; ++g) {
-                float x[8];
-                const int64_t off = (((int64_t)li * Hq + (h * r + g)) * Tq + j) * d + slot * 8;
-                load8(q + off * EB, QT{}, x);
+            // the r heads of the GQA block, eight loads in flight at a time
+            for (int g0 = 0; g0 < r; g0 += 8) {
+                Raw8<QT> raw[8];
 #pragma unroll
-                for (int i = 0; i < 8; ++i) qt[i] += (double)x[i];
+                for (int u = 0; u < 8; ++u) {
+                    zero_raw(raw[u]);
+                    if (g0 + u < r) {
+                        const int64_t off =
+                            (((int64_t)li * Hq + (h * r + g0 + u)) * Tq + j) * d + slot * 8;
+                        load_raw(q + off * EB, raw[u]);
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    float x[8];
+                    widen(raw[u], x);  // heads past the block were zero-filled
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) qt[i] += (double)x[i];
+                }
             }
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
@@ -88,7 +101,7 @@ __global__ void __launch_bounds__(kBlock) query_fold_kernel(const ScoreArgs a, c
 }
 
 // ------------------------------------------------------------------ mean-query GEMV
-constexpr int kGroupsPerWave = 8;
+constexpr int kGroupsPerWave = 4;  // scored together: their key loads are all in flight at once
 
 // grid (ceil(T / (4 * kGroupsPerWave)), n_layers); dynamic LDS: H_k*d doubles (q-bar).
 __global__ void __launch_bounds__(kBlock) score_mean_query_kernel(const ScoreArgs a) {
@@ -96,37 +109,57 @@ __global__ void __launch_bounds__(kBlock) score_mean_query_kernel(const ScoreArg
     const int li = blockIdx.y;
     const int HD = a.n_kv_heads * a.head_dim;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const float* keys = a.keys + ((int64_t)(a.layer0 + li) * a.capacity_groups) * HD;
+    const int t0 = (blockIdx.x * (kBlock / 64) + wave) * kGroupsPerWave;
+    const bool live = t0 < a.n_groups;  // uniform per wave
+    // The first key loads do not depend on the query: issue them before q-bar is staged.
+    f32x4 kx[kGroupsPerWave];
+    auto load_keys = [&](int e) {
+#pragma unroll
+        for (int g = 0; g < kGroupsPerWave; ++g) {
+            const int t = min(t0 + g, a.n_groups - 1);  // the tail re-reads the last group
+            kx[g] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+            if (live && e < HD) kx[g] = *reinterpret_cast<const f32x4*>(keys + (int64_t)t * HD + e);
+        }
+    };
+    load_keys(lane * 4);
+
     for (int e = tid; e < HD; e += kBlock) qbar[e] = a.ws_qbar[(int64_t)li * HD + e];
     double nq2 = 0.0;
     for (int hh = 0; hh < a.n_kv_heads; ++hh) nq2 += a.ws_qnorm2[(int64_t)li * a.n_kv_heads + hh];
     const double nq = sqrt(nq2);
     __syncthreads();
+    if (!live) return;  // no barrier follows
 
-    const float* keys = a.keys + ((int64_t)(a.layer0 + li) * a.capacity_groups) * HD;
-    const int t0 = (blockIdx.x * (kBlock / 64) + wave) * kGroupsPerWave;
-    for (int gi = 0; gi < kGroupsPerWave; ++gi) {
-        const int t = t0 + gi;
-        if (t >= a.n_groups) break;  // uniform per wave
-        const float* key = keys + (int64_t)t * HD;
-        double dot = 0.0, nk2 = 0.0;
-        for (int e = lane * 4; e < HD; e += 256) {
-            const f32x4 kx = *reinterpret_cast<const f32x4*>(key + e);
+    double dot[kGroupsPerWave], nk2[kGroupsPerWave];
+#pragma unroll
+    for (int g = 0; g < kGroupsPerWave; ++g) dot[g] = nk2[g] = 0.0;
+    for (int e = lane * 4; e < HD; e += 256) {
+        f32x4 cur[kGroupsPerWave];
+#pragma unroll
+        for (int g = 0; g < kGroupsPerWave; ++g) cur[g] = kx[g];
+        load_keys(e + 256);  // next chunk in flight while this one is accumulated
+        double qv[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) qv[i] = qbar[e + i];
+#pragma unroll
+        for (int g = 0; g < kGroupsPerWave; ++g) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const double kd = (double)kx[i];
-                dot = fma(qbar[e + i], kd, dot);
-                nk2 = fma(kd, kd, nk2);
+                const double kd = (double)cur[g][i];
+                dot[g] = fma(qv[i], kd, dot[g]);
+                nk2[g] = fma(kd, kd, nk2[g]);
             }
         }
-        dot = wave_sum_f64(dot);
-        nk2 = wave_sum_f64(nk2);
-        if (lane == 0) {
-            double s = dot;
-            if (a.sim == TOM_SIM_COSINE) {
-                const double nk = sqrt(nk2);
-                s = dot / (fmax(nq, 1e-12) * fmax(nk, 1e-12));
-            }
-            a.scores[(int64_t)li * a.score_stride + t] = (float)s;
+    }
+#pragma unroll
+    for (int g = 0; g < kGroupsPerWave; ++g) {
+        const double dsum = wave_sum_f64(dot[g]);
+        const double nsum = wave_sum_f64(nk2[g]);
+        if (lane == 0 && t0 + g < a.n_groups) {
+            double s = dsum;
+            if (a.sim == TOM_SIM_COSINE) s = dsum / (fmax(nq, 1e-12) * fmax(sqrt(nsum), 1e-12));
+            a.scores[(int64_t)li * a.score_stride + t0 + g] = (float)s;
         }
     }
 }
