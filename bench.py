@@ -61,7 +61,7 @@ def measured_traffic(kernel, workload):
     return None
 
 
-def cpu_baseline(w, batches_cpu, q_cpu, threads):
+def cpu_baseline(w, batches_cpu, q_cpu, threads, qaxis=0):
     """The oracle, as it stands, on a bounded sample of the same workload: the given append
     batches (all layers) and one retrieval over what they stored.  Threads split layers."""
     from concurrent.futures import ThreadPoolExecutor
@@ -74,7 +74,8 @@ def cpu_baseline(w, batches_cpu, q_cpu, threads):
     dt = {"f32": 0, "bf16": 1, "f16": 2}[w.dtype]
     F = sum(b[0].shape[0] for b in batches_cpu)
     cfg = orc.make_config(w.n_layers, w.n_kv_heads, w.n_q_heads, w.head_dim, w.group_tokens,
-                          w.qgroup, F, in_dtype=dt, out_dtype=dt, sim=1 if w.sim == "cosine" else 0)
+                          w.qgroup, F, qaxis=qaxis, in_dtype=dt, out_dtype=dt,
+                          sim=1 if w.sim == "cosine" else 0)
     st = orc.new_store(cfg)
     L = w.n_layers
     threads = max(1, min(threads, L))
@@ -126,6 +127,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="C3", choices=["C2", "C3", "C4", "C5"])
     ap.add_argument("--frames-per-append", type=int, default=0, help="override the workload's batch")
+    ap.add_argument("--qaxis", default="head_dim", choices=["head_dim", "tokens"],
+                    help="tokens = the paper's Eq. 9 (scale/zero per channel over the G tokens)")
+    ap.add_argument("--group-tokens", type=int, default=0, help="override G (the paper keeps 50)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-batches", type=int, default=12)
     args = ap.parse_args()
@@ -143,15 +147,21 @@ def main():
     torch.cuda.set_device(0)
     dev = "cuda:0"
     w = synth_kv.WORKLOADS[args.workload]
+    if args.group_tokens:
+        w = synth_kv.scaled(w, group_tokens=args.group_tokens)
+    tok = args.qaxis == "tokens"
     fpa = args.frames_per_append or (w.frames_per_append if w.frames_per_append > 1 else 1)
     fpa = min(fpa, w.n_frames)
     T = (w.n_frames // fpa) * fpa
     eb = 4 if w.dtype == "f32" else 2
     dtc = {"f32": oqm.TOM_F32, "bf16": oqm.TOM_BF16, "f16": oqm.TOM_F16}[w.dtype]
     cfg = oqm.make_config(w.n_layers, w.n_kv_heads, w.n_q_heads, w.head_dim, w.group_tokens,
-                          w.qgroup, T, in_dtype=dtc, out_dtype=dtc,
+                          w.qgroup, T, qaxis=oqm.TOM_QAXIS_TOKENS if tok else oqm.TOM_QAXIS_HEAD_DIM,
+                          in_dtype=dtc, out_dtype=dtc,
                           sim=oqm.TOM_SIM_COSINE if w.sim == "cosine" else oqm.TOM_SIM_DOT)
     mem = oqm.Memory.allocate(cfg, dev)
+    if tok:   # byte model: one (scale, zero) pair per channel and tile instead of per gs elements
+        w = synth_kv.scaled(w, qgroup=w.group_tokens)
     L = w.n_layers
 
     # distinct input batches, more than the 256 MB last-level cache can hold, rotated per step
@@ -248,7 +258,10 @@ def main():
         "config": {
             "workload": f"{w.name}: {L} layers, {w.n_kv_heads} KV heads ({w.n_q_heads} query heads), "
                         f"head_dim {w.head_dim}, {w.dtype} K/V, {T} frames x {w.group_tokens} tokens stored, "
-                        f"{fpa} frames per quantize-append, 4-bit codes, quant-group {w.qgroup} over head_dim, "
+                        f"{fpa} frames per quantize-append, 4-bit codes, "
+                        + (f"scale/zero per channel over the {w.group_tokens} tokens, " if tok else
+                           f"quant-group {w.qgroup} over head_dim, ") +
+                        ""
                         f"{w.t_q}-token query, top-{k_eff} groups dequant-gathered to {w.dtype}",
             "value_recipe": w.kind, "score_path": "token_gemm" if path == oqm.TOM_SCORE_TOKEN_GEMM else "mean_query",
             "input_batches_rotated": n_batches,
@@ -281,7 +294,7 @@ def main():
         host = [(k.cpu(), v.cpu()) for k, v in batches[:min(nb, n_batches)]]
         sample = [host[i % len(host)] for i in range(nb)]      # cycle the resident batches
         threads = min(16, os.cpu_count() or 1)
-        out["cpu_baseline"] = cpu_baseline(w, sample, queries[0].cpu(), threads)
+        out["cpu_baseline"] = cpu_baseline(w, sample, queries[0].cpu(), threads, 1 if tok else 0)
         out["cpu_baseline"]["value"] = round(out["cpu_baseline"]["value"], 3)
         del out["cpu_baseline"]["tokens_per_s_append"]
     print(json.dumps(out))

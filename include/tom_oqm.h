@@ -89,7 +89,8 @@ typedef struct {
     int32_t n_q_heads;       /* H_q, a multiple of H_k (GQA blocks of consecutive heads) */
     int32_t head_dim;        /* d, a multiple of 8, at most 2048                         */
     int32_t group_tokens;    /* G >= 1, tokens per frame-group                           */
-    int32_t qgroup;          /* gs in {8, 16, 32, 64, 128}, divides d (HEAD_DIM axis)    */
+    int32_t qgroup;          /* gs in {8, 16, 32, 64, 128}, divides d (HEAD_DIM axis);
+                                ignored on the TOKENS axis                               */
     int32_t qaxis;           /* tom_qaxis_t                                              */
     int32_t bits;            /* 4                                                        */
     int32_t capacity_groups; /* T_cap: frame-groups the bound storage can hold           */
@@ -141,7 +142,8 @@ int32_t tom_oqm_k_from_budget(int64_t budget_tokens, int32_t group_tokens, int32
  *
  * Quantizes n_frames frame-groups of layers [layer0, layer0 + n_layers) and
  * writes them to group slots T .. T + n_frames - 1, T = tom_oqm_num_groups(h).
- * Per quant-group: m = min, s = (max - min) / 15 in float32;
+ * Per quant-group (gs consecutive channels of one token, or with qaxis TOKENS
+ * all G tokens of one channel): m = min, s = (max - min) / 15 in float32;
  * code = clamp(round_half_even(d * inv), 0, 15) with d = float32(x - m),
  * inv = float32(1 / s) computed once per quant-group, and the product d * inv
  * not rounded before the rounding to an integer; s below FLT_MIN (e.g.

@@ -45,14 +45,15 @@ static tom_status_t check_config(const tom_oqm_config_t* c) {
         if (c->bits == 2) return fail(TOM_ERR_UNSUPPORTED, "2-bit codes are not built yet");
         return fail(TOM_ERR_INVALID_ARG, "bits must be 4");
     }
-    if (c->qaxis == TOM_QAXIS_TOKENS)
-        return fail(TOM_ERR_UNSUPPORTED, "per-channel (token axis) quantization is not built yet");
-    if (c->qaxis != TOM_QAXIS_HEAD_DIM) return fail(TOM_ERR_INVALID_ARG, "qaxis is not a tom_qaxis_t");
-    const int gs = c->qgroup;
-    if (gs < 1 || c->head_dim % gs)
-        return fail(TOM_ERR_INVALID_ARG, "qgroup %d does not divide head_dim %d", gs, c->head_dim);
-    if (gs != 8 && gs != 16 && gs != 32 && gs != 64 && gs != 128)
-        return fail(TOM_ERR_UNSUPPORTED, "qgroup %d: the kernels cover 8, 16, 32, 64 and 128", gs);
+    if (c->qaxis != TOM_QAXIS_HEAD_DIM && c->qaxis != TOM_QAXIS_TOKENS)
+        return fail(TOM_ERR_INVALID_ARG, "qaxis is not a tom_qaxis_t");
+    if (c->qaxis == TOM_QAXIS_HEAD_DIM) {
+        const int gs = c->qgroup;
+        if (gs < 1 || c->head_dim % gs)
+            return fail(TOM_ERR_INVALID_ARG, "qgroup %d does not divide head_dim %d", gs, c->head_dim);
+        if (gs != 8 && gs != 16 && gs != 32 && gs != 64 && gs != 128)
+            return fail(TOM_ERR_UNSUPPORTED, "qgroup %d: the kernels cover 8, 16, 32, 64 and 128", gs);
+    }
     if ((int64_t)c->n_kv_heads * c->head_dim > 8192)
         return fail(TOM_ERR_UNSUPPORTED, "n_kv_heads * head_dim > 8192 is not covered by the score kernels");
     return TOM_OK;
@@ -183,6 +184,7 @@ tom_status_t tom_oqm_quantize_append(tom_oqm_t* h, int32_t layer0, int32_t n_lay
     a.n_layers = n_layers;
     a.n_frames = n_frames;
     a.first_group = h->n_groups;
+    a.qaxis = c.qaxis;
     const hipError_t e = launch_quantize_append(a, c.in_dtype, static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return fail(TOM_ERR_HIP, "quantize_append launch: %s", hipGetErrorString(e));
     if (commit) h->n_groups += n_frames;
@@ -314,6 +316,7 @@ tom_status_t tom_oqm_dequant_gather(const tom_oqm_t* h, int32_t layer0, int32_t 
     a.k = k;
     a.k_eff = k_eff;
     a.n_groups = h->n_groups;
+    a.qaxis = c.qaxis;
     const hipError_t e = launch_dequant_gather(a, c.out_dtype, static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return fail(TOM_ERR_HIP, "dequant_gather launch: %s", hipGetErrorString(e));
     return TOM_OK;

@@ -50,6 +50,7 @@ struct QuantArgs {
     float* keys;
     int32_t n_kv_heads, head_dim, group_tokens, qgroup, capacity_groups;
     int32_t layer0, n_layers, n_frames, first_group;
+    int32_t qaxis;
 };
 
 struct DequantArgs {
@@ -60,6 +61,7 @@ struct DequantArgs {
     void* v_out;
     int32_t n_kv_heads, head_dim, group_tokens, qgroup, capacity_groups;
     int32_t layer0, n_layers, k, k_eff, n_groups;
+    int32_t qaxis;
 };
 
 struct ScoreArgs {
@@ -77,6 +79,7 @@ struct ScoreArgs {
 
 // ---- launchers (each validates nothing: the API layer has done that) ------
 hipError_t launch_quantize_append(const QuantArgs& a, int in_dtype, hipStream_t s);
+hipError_t launch_quantize_append_tokens(const QuantArgs& a, int in_dtype, hipStream_t s);
 hipError_t launch_dequant_gather(const DequantArgs& a, int out_dtype, hipStream_t s);
 hipError_t launch_query_fold(const ScoreArgs& a, bool want_tokens, hipStream_t s);
 hipError_t launch_score_mean_query(const ScoreArgs& a, hipStream_t s);

@@ -18,7 +18,7 @@ namespace {
 
 // kUnroll: rows per lane whose loads are issued before any is converted; the host picks it
 // so that a whole tile is covered in one trip when it fits (13 trips of 16 rows for 196 x 128).
-template <typename OUT, int kUnroll>
+template <typename OUT, int kUnroll, bool TOKEN_AXIS>
 __global__ void __launch_bounds__(kBlock) dequant_gather_kernel(const DequantArgs a, const int lpg) {
     constexpr int EB = elem_bytes<OUT>::value;
     const int H = a.n_kv_heads, d = a.head_dim, G = a.group_tokens;
@@ -36,16 +36,23 @@ __global__ void __launch_bounds__(kBlock) dequant_gather_kernel(const DequantArg
     const int row0 = tid / lpr;
     const int slot = tid - row0 * lpr;
     if (row0 >= rpp) return;
-    const int ng = lpr / lpg;
+    const int ng = TOKEN_AXIS ? 0 : lpr / lpg;
 
     const int64_t tile = (((int64_t)(a.layer0 + li) * 2 + kv) * a.capacity_groups + t) * H + h;
     const char* codes_t = reinterpret_cast<const char*>(a.codes + tile * ((int64_t)G * d / 2));
-    const f32x2* meta_t = reinterpret_cast<const f32x2*>(a.meta) + tile * ((int64_t)G * ng);
+    // token axis (Eq. 9): one pair per channel, d pairs per tile; else G * d/gs pairs
+    const f32x2* meta_t =
+        reinterpret_cast<const f32x2*>(a.meta) + tile * (TOKEN_AXIS ? (int64_t)d : (int64_t)G * ng);
+    f32x2 ch[8];  // token axis: the pairs of this lane's 8 channels, loaded once
+    if (TOKEN_AXIS) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) ch[i] = meta_t[slot * 8 + i];
+    }
     char* out = static_cast<char*>(kv ? a.v_out : a.k_out) +
                 ((((int64_t)li * H + h) * a.k + r) * G) * (int64_t)d * EB;
     // offsets inside one tile fit 32 bits (G * d * 4 < 2^31 is checked on the host)
     const uint32_t code_lane = ((uint32_t)row0 * lpr + slot) * 4u;
-    const int meta_lane = row0 * ng + slot / lpg;
+    const int meta_lane = TOKEN_AXIS ? 0 : row0 * ng + slot / lpg;
     const uint32_t out_lane = ((uint32_t)row0 * d + slot * 8u) * EB;
 
     for (int r0 = 0; r0 + row0 < G; r0 += kUnroll * rpp) {
@@ -58,7 +65,7 @@ __global__ void __launch_bounds__(kBlock) dequant_gather_kernel(const DequantArg
             sm[u] = f32x2{0.0f, 0.0f};
             if (rb + row0 < G) {
                 w[u] = *reinterpret_cast<const uint32_t*>(codes_t + (code_lane + (uint32_t)rb * lpr * 4u));
-                sm[u] = meta_t[meta_lane + rb * ng];
+                if (!TOKEN_AXIS) sm[u] = meta_t[meta_lane + rb * ng];
             }
         }
 #pragma unroll
@@ -69,7 +76,8 @@ __global__ void __launch_bounds__(kBlock) dequant_gather_kernel(const DequantArg
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
                     const float c = (float)((w[u] >> (4 * i)) & 15u);
-                    x[i] = __builtin_fmaf(c, sm[u][0], sm[u][1]);  // Eq. 11, rounded once to float32
+                    const f32x2 p = TOKEN_AXIS ? ch[i] : sm[u];
+                    x[i] = __builtin_fmaf(c, p[0], p[1]);  // Eq. 11, rounded once to float32
                 }
                 store8(out + (out_lane + (uint32_t)rb * d * EB), OUT{}, x);
             }
@@ -83,13 +91,18 @@ hipError_t launch_t(const DequantArgs& a, hipStream_t s) {
     const dim3 grid(a.k_eff, 2 * a.n_kv_heads, a.n_layers), block(kBlock);
     const int rpp = kBlock / (a.head_dim / 8);
     const int trips = (a.group_tokens + rpp - 1) / rpp;  // row passes per tile
-    const int lpg = a.qgroup / 8;
-    if (trips <= 4)
-        dequant_gather_kernel<OUT, 4><<<grid, block, 0, s>>>(a, lpg);
-    else if (trips <= 8 || trips > 13)
-        dequant_gather_kernel<OUT, 8><<<grid, block, 0, s>>>(a, lpg);
-    else
-        dequant_gather_kernel<OUT, 13><<<grid, block, 0, s>>>(a, lpg);
+    const int lpg = a.qgroup / 8;  // unused for the token axis
+    const bool tok = a.qaxis == TOM_QAXIS_TOKENS;
+    if (trips <= 4) {
+        if (tok) dequant_gather_kernel<OUT, 4, true><<<grid, block, 0, s>>>(a, 1);
+        else dequant_gather_kernel<OUT, 4, false><<<grid, block, 0, s>>>(a, lpg);
+    } else if (trips <= 8 || trips > 13) {
+        if (tok) dequant_gather_kernel<OUT, 8, true><<<grid, block, 0, s>>>(a, 1);
+        else dequant_gather_kernel<OUT, 8, false><<<grid, block, 0, s>>>(a, lpg);
+    } else {
+        if (tok) dequant_gather_kernel<OUT, 13, true><<<grid, block, 0, s>>>(a, 1);
+        else dequant_gather_kernel<OUT, 13, false><<<grid, block, 0, s>>>(a, lpg);
+    }
     return hipGetLastError();
 }
 

@@ -146,6 +146,24 @@ __device__ __forceinline__ float rcp_exact(float s) {
     return __builtin_fmaf(e, r, r);
 }
 
+// t[i] = fma(x_i - m, 1/s, 2^23): the exact product is rounded once, to an integer,
+// ties to even, and that integer sits in the low mantissa bits:
+// bits(t) = 0x4B000000 | code.  Packs 8 codes, even channel in the low nibble.
+__device__ __forceinline__ uint32_t pack8(const float (&t)[8]) {
+    uint32_t m[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) m[i] = __float_as_uint(t[i]);
+    // byte 0 of (m[2j+1] << 4 | m[2j]) is packed byte j; bits 8..23 of it are zero
+    const uint32_t b01 = (m[1] << 4) | m[0];
+    const uint32_t b23 = (m[3] << 4) | m[2];
+    const uint32_t b45 = (m[5] << 4) | m[4];
+    const uint32_t b67 = (m[7] << 4) | m[6];
+    const uint32_t lo = (b23 << 8) | b01;  // bytes 0, 1 valid
+    const uint32_t hi = (b67 << 8) | b45;
+    return __builtin_amdgcn_perm(hi, lo, 0x05040100u);  // {lo.b0, lo.b1, hi.b0, hi.b1}
+}
+
+
 template <typename T> struct elem_bytes;
 template <> struct elem_bytes<In_f32> { static constexpr int value = 4; };
 template <> struct elem_bytes<In_bf16> { static constexpr int value = 2; };

@@ -27,23 +27,6 @@ namespace {
 
 constexpr int kUnroll = 2;  // token rows per lane and loop trip
 
-// t[i] = fma(x_i - m, 1/s, 2^23): the exact product is rounded once, to an integer,
-// ties to even, and that integer sits in the low mantissa bits:
-// bits(t) = 0x4B000000 | code.  Packs 8 codes, even channel in the low nibble.
-__device__ __forceinline__ uint32_t pack8(const float (&t)[8]) {
-    uint32_t m[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) m[i] = __float_as_uint(t[i]);
-    // byte 0 of (m[2j+1] << 4 | m[2j]) is packed byte j; bits 8..23 of it are zero
-    const uint32_t b01 = (m[1] << 4) | m[0];
-    const uint32_t b23 = (m[3] << 4) | m[2];
-    const uint32_t b45 = (m[5] << 4) | m[4];
-    const uint32_t b67 = (m[7] << 4) | m[6];
-    const uint32_t lo = (b23 << 8) | b01;  // bytes 0, 1 valid
-    const uint32_t hi = (b67 << 8) | b45;
-    return __builtin_amdgcn_perm(hi, lo, 0x05040100u);  // {lo.b0, lo.b1, hi.b0, hi.b1}
-}
-
 template <typename IN, int LPG, bool SEPARATE_SUMMARY>
 __global__ void __launch_bounds__(kBlock) quantize_append_kernel(const QuantArgs a) {
     constexpr int EB = elem_bytes<IN>::value;
@@ -202,6 +185,7 @@ hipError_t launch_lpg(const QuantArgs& a, hipStream_t s) {
 }  // namespace
 
 hipError_t launch_quantize_append(const QuantArgs& a, int in_dtype, hipStream_t s) {
+    if (a.qaxis == TOM_QAXIS_TOKENS) return launch_quantize_append_tokens(a, in_dtype, s);
     switch (in_dtype) {
         case TOM_F32: return launch_lpg<In_f32>(a, s);
         case TOM_BF16: return launch_lpg<In_bf16>(a, s);

@@ -48,7 +48,7 @@ def test_sizes_follow_the_documented_layout(oqm):
     ("head_dim", 100, "INVALID"), ("qgroup", 48, "INVALID"), ("qgroup", 4, "UNSUPPORTED"),
     ("bits", 3, "INVALID"), ("bits", 2, "UNSUPPORTED"), ("n_q_heads", 27, "INVALID"),
     ("group_tokens", 0, "INVALID"), ("capacity_groups", 0, "INVALID"), ("in_dtype", 7, "INVALID"),
-    ("sim", 2, "INVALID"), ("qaxis", 1, "UNSUPPORTED"), ("qaxis", 5, "INVALID")])
+    ("sim", 2, "INVALID"), ("qaxis", 5, "INVALID")])
 def test_bad_configurations_are_rejected(oqm, field, value, status):
     cfg = oqm.make_config(2, 4, 28, 128, 196, 64, 16)
     setattr(cfg, field, value)
@@ -106,6 +106,14 @@ def test_host_side_validation_before_any_launch(oqm):
         assert oqm.tom_oqm_num_groups(h) == 0
     finally:
         oqm.tom_oqm_destroy(h)
+
+
+def test_token_axis_sizes(oqm):
+    cfg = oqm.make_config(28, 4, 28, 128, 50, 64, 100, qaxis=oqm.TOM_QAXIS_TOKENS)
+    cfg.qgroup = 7                                        # ignored on the token axis
+    s = oqm.tom_oqm_query_sizes(cfg)
+    tiles = 28 * 2 * 100 * 4
+    assert s.codes == tiles * 50 * 64 and s.meta == tiles * 128 * 2 * 4
 
 
 def test_workspace_size(oqm):

@@ -20,8 +20,9 @@ def oqm():
     return m
 
 
-def _stream_and_check(oqm, w, frames_per_call, k=None, path=None, want_tokens=False, out_dtype=None):
-    st, mem = H.pair_for(oqm, w, out_dtype=out_dtype)
+def _stream_and_check(oqm, w, frames_per_call, k=None, path=None, want_tokens=False, out_dtype=None,
+                      qaxis=0):
+    st, mem = H.pair_for(oqm, w, out_dtype=out_dtype, qaxis=qaxis)
     try:
         f = 0
         while f < w.n_frames:
@@ -72,6 +73,17 @@ def test_shapes_dtypes_and_ragged_tails(oqm, G, d, gs, dt, H_k, H_q):
     r = _stream_and_check(oqm, synth_kv.scaled(w, sim="dot", t_q=17), 11, k=6,
                           path=oqm.TOM_SCORE_TOKEN_GEMM, want_tokens=True)
     assert r["k_eff"] == 6
+
+
+@pytest.mark.parametrize("G,d,dt,H_k,H_q", [
+    (50, 128, "f16", 4, 28),           # the paper's setting: 50-token groups, FP16, per-channel scale
+    (196, 128, "bf16", 4, 28), (1, 64, "f32", 1, 1), (13, 96, "bf16", 3, 6), (300, 64, "f16", 2, 2),
+    (33, 8, "f32", 5, 5), (40, 512, "bf16", 1, 3)])
+def test_token_axis_quantizer(oqm, G, d, dt, H_k, H_q):
+    """Eq. 9 as printed: scale and zero per head and channel over the G tokens of a group."""
+    w = synth_kv.Workload("X", 2, H_k, H_q, d, G, 9, 64, 5, 4, dt, "cosine", 300 + G + d, "outlier", 9)
+    r = _stream_and_check(oqm, w, 4, qaxis=1)
+    assert r["k_eff"] == 4 and r["loose_rows"] == 0
 
 
 def test_mixed_in_out_dtypes(oqm):
