@@ -6,8 +6,9 @@
 // 8 channels of one token row), but the min/max run down the token rows: each lane keeps
 // 8 running minima and maxima over its rows, the 256/(d/8) row slots of the workgroup are
 // combined through LDS, one thread per channel derives scale, reciprocal and zero point,
-// and a second sweep over the tile (served by the caches: the tile was read a moment ago)
-// quantizes and packs.  HBM traffic per element: 2 B read + 0.5 B written + 8/G B of
+// and a second sweep quantizes and packs.  When a lane's share of the tile fits a few
+// registers (HOLD rows: up to 13 x 16 B) the rows stay in registers between the sweeps;
+// otherwise the second sweep reads the tile again (from the caches: it was read a moment ago).  HBM traffic per element: 2 B read + 0.5 B written + 8/G B of
 // (scale, zero) pairs.
 #include "oqm_common.h"
 #include "oqm_device.h"
@@ -17,7 +18,7 @@ namespace {
 
 constexpr int kUnroll = 2;
 
-template <typename IN, bool SEPARATE_SUMMARY>
+template <typename IN, bool SEPARATE_SUMMARY, int HOLD>
 __global__ void __launch_bounds__(kBlock) quantize_append_tokens_kernel(const QuantArgs a) {
     constexpr int EB = elem_bytes<IN>::value;
     const int H = a.n_kv_heads, d = a.head_dim, G = a.group_tokens;
@@ -60,26 +61,40 @@ __global__ void __launch_bounds__(kBlock) quantize_append_tokens_kernel(const Qu
 
     // ---- sweep 1: per-channel min / max (and the key sums) down the token rows
     const int step = kUnroll * rpp;
-    for (int r0 = 0; active && r0 + row0 < G; r0 += step) {
-        Raw8<IN> raw[kUnroll];
+    constexpr int kHeld = HOLD > 0 ? HOLD : 1;
+    Raw8<IN> held[kHeld];
+    auto reduce_row = [&](const Raw8<IN>& raw) {
+        float x[8];
+        widen(raw, x);
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u)
-            if (r0 + u * rpp + row0 < G) load_raw(src + (in_lane + (uint32_t)(r0 + u * rpp) * in_row_bytes), raw[u]);
+        for (int i = 0; i < 8; ++i) {
+            mn[i] = fminf(mn[i], x[i]);
+            mx[i] = fmaxf(mx[i], x[i]);
+        }
+        if (!SEPARATE_SUMMARY && do_sum) {
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            if (r0 + u * rpp + row0 < G) {
-                float x[8];
-                widen(raw[u], x);
+            for (int i = 0; i < 8; ++i) acc[i] += (double)x[i];
+        }
+    };
+    if (HOLD > 0) {
 #pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    mn[i] = fminf(mn[i], x[i]);
-                    mx[i] = fmaxf(mx[i], x[i]);
-                }
-                if (!SEPARATE_SUMMARY && do_sum) {
+        for (int u = 0; u < kHeld; ++u) {
+            zero_raw(held[u]);
+            if (active && u * rpp + row0 < G) load_raw(src + (in_lane + (uint32_t)(u * rpp) * in_row_bytes), held[u]);
+        }
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) acc[i] += (double)x[i];
-                }
-            }
+        for (int u = 0; u < kHeld; ++u)
+            if (active && u * rpp + row0 < G) reduce_row(held[u]);
+    } else {
+        for (int r0 = 0; active && r0 + row0 < G; r0 += step) {
+            Raw8<IN> raw[kUnroll];
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u)
+                if (r0 + u * rpp + row0 < G)
+                    load_raw(src + (in_lane + (uint32_t)(r0 + u * rpp) * in_row_bytes), raw[u]);
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u)
+                if (r0 + u * rpp + row0 < G) reduce_row(raw[u]);
         }
     }
     if (active) {
@@ -117,22 +132,27 @@ __global__ void __launch_bounds__(kBlock) quantize_append_tokens_kernel(const Qu
             zm[i] = v[0];
             zi[i] = v[1];
         }
-        for (int r0 = 0; r0 + row0 < G; r0 += step) {
-            Raw8<IN> raw[kUnroll];
+        auto quantize_row = [&](const Raw8<IN>& raw, int rb) {
+            float x[8], tq[8];
+            widen(raw, x);
 #pragma unroll
-            for (int u = 0; u < kUnroll; ++u)
-                if (r0 + u * rpp + row0 < G)
-                    load_raw(src + (in_lane + (uint32_t)(r0 + u * rpp) * in_row_bytes), raw[u]);
+            for (int i = 0; i < 8; ++i) tq[i] = __builtin_fmaf(__fsub_rn(x[i], zm[i]), zi[i], 8388608.0f);
+            *reinterpret_cast<uint32_t*>(codes_t + (code_lane + (uint32_t)rb * lpr * 4u)) = pack8(tq);
+        };
+        if (HOLD > 0) {
 #pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
-                const int rb = r0 + u * rpp;
-                if (rb + row0 < G) {
-                    float x[8], tq[8];
-                    widen(raw[u], x);
+            for (int u = 0; u < kHeld; ++u)
+                if (u * rpp + row0 < G) quantize_row(held[u], u * rpp);
+        } else {
+            for (int r0 = 0; r0 + row0 < G; r0 += step) {
+                Raw8<IN> raw[kUnroll];
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) tq[i] = __builtin_fmaf(__fsub_rn(x[i], zm[i]), zi[i], 8388608.0f);
-                    *reinterpret_cast<uint32_t*>(codes_t + (code_lane + (uint32_t)rb * lpr * 4u)) = pack8(tq);
-                }
+                for (int u = 0; u < kUnroll; ++u)
+                    if (r0 + u * rpp + row0 < G)
+                        load_raw(src + (in_lane + (uint32_t)(r0 + u * rpp) * in_row_bytes), raw[u]);
+#pragma unroll
+                for (int u = 0; u < kUnroll; ++u)
+                    if (r0 + u * rpp + row0 < G) quantize_row(raw[u], r0 + u * rpp);
             }
         }
     }
@@ -161,16 +181,26 @@ __global__ void __launch_bounds__(kBlock) quantize_append_tokens_kernel(const Qu
     }
 }
 
-template <typename IN>
-hipError_t launch_t(const QuantArgs& a, hipStream_t s) {
-    if (a.n_frames == 0 || a.n_layers == 0) return hipSuccess;
+template <typename IN, int HOLD>
+hipError_t launch_h(const QuantArgs& a, hipStream_t s) {
     const dim3 grid(a.n_kv_heads, 2 * a.n_layers, a.n_frames);
     const size_t lds = (size_t)a.head_dim * sizeof(f32x2);
     if (a.ksum != a.k)
-        quantize_append_tokens_kernel<IN, true><<<grid, dim3(kBlock), lds, s>>>(a);
+        quantize_append_tokens_kernel<IN, true, HOLD><<<grid, dim3(kBlock), lds, s>>>(a);
     else
-        quantize_append_tokens_kernel<IN, false><<<grid, dim3(kBlock), lds, s>>>(a);
+        quantize_append_tokens_kernel<IN, false, HOLD><<<grid, dim3(kBlock), lds, s>>>(a);
     return hipGetLastError();
+}
+
+template <typename IN>
+hipError_t launch_t(const QuantArgs& a, hipStream_t s) {
+    if (a.n_frames == 0 || a.n_layers == 0) return hipSuccess;
+    const int rpp = kBlock / (a.head_dim / 8);
+    const int trips = (a.group_tokens + rpp - 1) / rpp;  // rows per lane
+    if (trips <= 4) return launch_h<IN, 4>(a, s);
+    if (trips <= 8) return launch_h<IN, 8>(a, s);
+    if (trips <= 13 && sizeof(Raw8<IN>) <= 16) return launch_h<IN, 13>(a, s);
+    return launch_h<IN, 0>(a, s);
 }
 
 }  // namespace
