@@ -243,6 +243,46 @@ tom_status_t tom_oqm_dequant_gather(const tom_oqm_t* h, int32_t layer0, int32_t 
                                     const int32_t* idx_device, int32_t k, int32_t k_eff,
                                     void* k_out_device, void* v_out_device, void* hip_stream);
 
+/*
+ * Active-KV assembly with the system-token prefix (Sec. 3.4: the memory is a dual
+ * structure, system tokens stay in 16 bits while visual groups are quantized; supplement
+ * "Cache reconstruction for decoding": the KV slices of the selected groups and the system
+ * prompt tokens are assembled into one cache).
+ * Like tom_oqm_dequant_gather, but every head's buffer has prefix_rows extra token rows in
+ * front of the gathered groups:
+ *   k_out, v_out  device, [n_layers][H_k][prefix_rows + k * G][d] of cfg.out_dtype;
+ *                 group of rank r goes to rows [prefix_rows + r*G, prefix_rows + (r+1)*G)
+ *   sys_k, sys_v  device, [n_layers][H_k][prefix_rows][d] of cfg.out_dtype (already in the
+ *                 model's 16-bit format: they are copied, not re-quantized), or both NULL
+ *                 to leave rows [0, prefix_rows) as they are (e.g. written once per session).
+ * Errors as for tom_oqm_dequant_gather; prefix_rows < 0 or only one of sys_k / sys_v given
+ * is INVALID_ARG.
+ */
+tom_status_t tom_oqm_assemble_active(const tom_oqm_t* h, int32_t layer0, int32_t n_layers,
+                                     const int32_t* idx_device, int32_t k, int32_t k_eff,
+                                     int32_t prefix_rows, const void* sys_k_device,
+                                     const void* sys_v_device, void* k_out_device,
+                                     void* v_out_device, void* hip_stream);
+
+/*
+ * One call per question (supplement "Question-guided single-pass retrieval" and "Cache
+ * reconstruction for decoding": the matching cost is paid once per question and the
+ * per-layer indices are reused for all decoding steps): tom_oqm_score_groups, then
+ * tom_oqm_topk (ascending index order, k_eff = min(k, T)), then tom_oqm_assemble_active,
+ * queued back to back on one stream.  All three argument sets are validated before the
+ * first kernel is queued.  `scores` ([n_layers][score_stride]) and `idx` ([n_layers][k])
+ * are outputs the caller may inspect or reuse; the other arguments are those of the three
+ * calls.  No allocation, no memset, no synchronisation: the call can be captured in a HIP
+ * graph.
+ */
+tom_status_t tom_oqm_retrieve(const tom_oqm_t* h, int32_t layer0, int32_t n_layers,
+                              const void* q_device, int32_t q_dtype, int32_t t_q, int32_t k,
+                              int32_t path, float* scores_device, int64_t score_stride,
+                              int32_t* idx_device, int32_t prefix_rows, const void* sys_k_device,
+                              const void* sys_v_device, void* k_out_device, void* v_out_device,
+                              void* workspace_device, size_t workspace_bytes, int32_t* k_eff_host,
+                              void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -484,6 +484,50 @@ int32_t tomref_topk(const float* scores, int64_t score_stride, int32_t n_rows, i
     return k_eff;
 }
 
+/* Active KV with the system-token prefix (Sec. 3.4 dual-structure memory; supplement "Cache
+ * reconstruction for decoding"): per layer and head the buffer holds prefix_rows rows of
+ * system tokens, copied unchanged from sys_k / sys_v ([n_layers][H_k][prefix_rows][d], out
+ * dtype; NULL = rows left untouched), followed by the gathered groups as in
+ * tomref_dequant_gather.  k_out, v_out: [n_layers][H_k][prefix_rows + k*G][d]. */
+int32_t tomref_dequant_gather(const tomref_config* cfg, const uint8_t* codes, const float* scale,
+                              const float* zero, int32_t n_groups, int32_t layer0,
+                              int32_t n_layers, const int32_t* idx, int32_t k, int32_t k_eff,
+                              void* k_out, void* v_out);
+int32_t tomref_assemble_active(const tomref_config* cfg, const uint8_t* codes, const float* scale,
+                               const float* zero, int32_t n_groups, int32_t layer0,
+                               int32_t n_layers, const int32_t* idx, int32_t k, int32_t k_eff,
+                               int32_t prefix_rows, const void* sys_k, const void* sys_v,
+                               void* k_out, void* v_out) {
+    if (!config_ok(cfg) || prefix_rows < 0 || k < 1 || n_layers < 0) return -1;
+    const int G = cfg->group_tokens, d = cfg->head_dim, H = cfg->n_kv_heads;
+    const size_t es = dtype_size(cfg->out_dtype);
+    const int64_t head_rows = (int64_t)prefix_rows + (int64_t)k * G;
+    /* gather into a plain [n_layers][H][k*G][d] buffer, then place each head block */
+    const size_t plain = (size_t)n_layers * H * (size_t)k * G * d * es;
+    char* tk = (char*)malloc(plain ? plain : 1);
+    char* tv = (char*)malloc(plain ? plain : 1);
+    if (!tk || !tv) { free(tk); free(tv); return -1; }
+    int32_t rc = tomref_dequant_gather(cfg, codes, scale, zero, n_groups, layer0, n_layers, idx, k,
+                                       k_eff, tk, tv);
+    if (rc == 0)
+        for (int li = 0; li < n_layers; ++li)
+            for (int h = 0; h < H; ++h) {
+                const int64_t hb = (int64_t)li * H + h;
+                char* dk = (char*)k_out + (size_t)(hb * head_rows) * d * es;
+                char* dv = (char*)v_out + (size_t)(hb * head_rows) * d * es;
+                if (sys_k && sys_v && prefix_rows > 0) {
+                    memcpy(dk, (const char*)sys_k + (size_t)(hb * prefix_rows) * d * es, (size_t)prefix_rows * d * es);
+                    memcpy(dv, (const char*)sys_v + (size_t)(hb * prefix_rows) * d * es, (size_t)prefix_rows * d * es);
+                }
+                const size_t used = (size_t)k_eff * G * d * es;   /* rows past k_eff*G stay untouched */
+                memcpy(dk + (size_t)prefix_rows * d * es, tk + (size_t)(hb * k * G) * d * es, used);
+                memcpy(dv + (size_t)prefix_rows * d * es, tv + (size_t)(hb * k * G) * d * es, used);
+            }
+    free(tk);
+    free(tv);
+    return rc;
+}
+
 /* Active-KV assembly (Eq. 13): for each layer and rank r < k_eff, dequantize
  * frame-group idx[layer][r] of K and of V (Eq. 11) into rows
  * [r*G, (r+1)*G) of the layer's active buffers.

@@ -92,6 +92,9 @@ def lib():
         L.tomref_dequant_gather.argtypes = [C.POINTER(Config), vp, f32p, f32p, i32, i32, i32,
                                             vp, i32, i32, vp, vp]
         L.tomref_dequant_gather.restype = i32
+        L.tomref_assemble_active.argtypes = [C.POINTER(Config), vp, f32p, f32p, i32, i32, i32,
+                                             vp, i32, i32, i32, vp, vp, vp, vp]
+        L.tomref_assemble_active.restype = i32
         _lib = L
     return _lib
 
@@ -266,6 +269,25 @@ def dequant_gather(st: Store, idx: np.ndarray, k_eff: int, layer0: int = 0, fill
                                      st.n_groups, layer0, nl, _p(idx), k, k_eff, _p(ko), _p(vo))
     if rc != 0:
         raise ValueError(f"tomref_dequant_gather failed rc={rc}")
+    return ko, vo
+
+
+def assemble_active(st: Store, idx: np.ndarray, k_eff: int, prefix_rows: int, sys_k=None, sys_v=None,
+                    layer0: int = 0, fill=None):
+    """Active KV with a system-token prefix: returns (K_act, V_act)
+    [n_layers][H_k][prefix_rows + k*G][d] in cfg.out_dtype."""
+    cfg = st.cfg
+    idx = np.ascontiguousarray(idx, np.int32)
+    nl, k = idx.shape
+    shape = (nl, cfg.n_kv_heads, prefix_rows + k * cfg.group_tokens, cfg.head_dim)
+    dt = _np_dtype(cfg.out_dtype)
+    ko = np.zeros(shape, dt) if fill is None else np.full(shape, fill, dt)
+    vo = ko.copy()
+    rc = lib().tomref_assemble_active(C.byref(cfg), _p(st.codes), _p(st.scale), _p(st.zero),
+                                      st.n_groups, layer0, nl, _p(idx), k, k_eff, prefix_rows,
+                                      _p(sys_k), _p(sys_v), _p(ko), _p(vo))
+    if rc != 0:
+        raise ValueError(f"tomref_assemble_active failed rc={rc}")
     return ko, vo
 
 

@@ -207,10 +207,13 @@ size_t tom_oqm_score_workspace_bytes(const tom_oqm_t* h, int32_t n_layers, int32
     return doubles * sizeof(double) + 16;
 }
 
-tom_status_t tom_oqm_score_groups(const tom_oqm_t* h, int32_t layer0, int32_t n_layers,
-                                  const void* q, int32_t q_dtype, int32_t t_q, float* scores,
-                                  int64_t score_stride, float* token_scores, int32_t path,
-                                  void* workspace, size_t workspace_bytes, void* hip_stream) {
+// Each hot-path call is "validate everything, then launch": `launch == false` stops after the
+// validation, which lets tom_oqm_retrieve check all three steps before it queues the first.
+static tom_status_t score_impl(const tom_oqm_t* h, int32_t layer0, int32_t n_layers,
+                               const void* q, int32_t q_dtype, int32_t t_q, float* scores,
+                               int64_t score_stride, float* token_scores, int32_t path,
+                               void* workspace, size_t workspace_bytes, void* hip_stream,
+                               bool launch) {
     if (!h) return fail(TOM_ERR_INVALID_ARG, "handle is NULL");
     if (!h->bound) return fail(TOM_ERR_NOT_BOUND, "tom_oqm_bind has not been called");
     if (tom_status_t st = check_layers(h, layer0, n_layers)) return st;
@@ -231,6 +234,7 @@ tom_status_t tom_oqm_score_groups(const tom_oqm_t* h, int32_t layer0, int32_t n_
     if (!workspace || workspace_bytes < need)
         return fail(TOM_ERR_INVALID_ARG, "workspace of %zu bytes needed, %zu given", need, workspace_bytes);
     if (!aligned16(workspace)) return fail(TOM_ERR_INVALID_ARG, "workspace must be 16-byte aligned");
+    if (!launch) return TOM_OK;
 
     const tom_oqm_config_t& c = h->cfg;
     const size_t hd = (size_t)c.n_kv_heads * c.head_dim;
@@ -265,9 +269,17 @@ tom_status_t tom_oqm_score_groups(const tom_oqm_t* h, int32_t layer0, int32_t n_
     return TOM_OK;
 }
 
-tom_status_t tom_oqm_topk(const float* scores, int64_t score_stride, int32_t n_rows,
-                          int32_t n_groups, int32_t k, int32_t order, int32_t* idx,
-                          int32_t* k_eff_host, void* hip_stream) {
+tom_status_t tom_oqm_score_groups(const tom_oqm_t* h, int32_t layer0, int32_t n_layers,
+                                  const void* q, int32_t q_dtype, int32_t t_q, float* scores,
+                                  int64_t score_stride, float* token_scores, int32_t path,
+                                  void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return score_impl(h, layer0, n_layers, q, q_dtype, t_q, scores, score_stride, token_scores, path,
+                      workspace, workspace_bytes, hip_stream, true);
+}
+
+static tom_status_t topk_impl(const float* scores, int64_t score_stride, int32_t n_rows,
+                              int32_t n_groups, int32_t k, int32_t order, int32_t* idx,
+                              int32_t* k_eff_host, void* hip_stream, bool launch) {
     if (k < 1) return fail(TOM_ERR_INVALID_ARG, "k must be >= 1");
     if (n_rows < 0 || n_groups < 0) return fail(TOM_ERR_INVALID_ARG, "n_rows and n_groups must be >= 0");
     if (score_stride < n_groups) return fail(TOM_ERR_INVALID_ARG, "score_stride < n_groups");
@@ -279,27 +291,41 @@ tom_status_t tom_oqm_topk(const float* scores, int64_t score_stride, int32_t n_r
     if (k_eff_host) *k_eff_host = k_eff;
     if (n_rows == 0 || k_eff == 0) return TOM_OK;
     if (!scores || !idx) return fail(TOM_ERR_INVALID_ARG, "scores and idx must be non-NULL");
+    if (!launch) return TOM_OK;
     const hipError_t e = launch_topk(scores, score_stride, n_rows, n_groups, k, k_eff, order, idx,
                                      static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return fail(TOM_ERR_HIP, "topk launch: %s", hipGetErrorString(e));
     return TOM_OK;
 }
 
-tom_status_t tom_oqm_dequant_gather(const tom_oqm_t* h, int32_t layer0, int32_t n_layers,
-                                    const int32_t* idx, int32_t k, int32_t k_eff, void* k_out,
-                                    void* v_out, void* hip_stream) {
+tom_status_t tom_oqm_topk(const float* scores, int64_t score_stride, int32_t n_rows,
+                          int32_t n_groups, int32_t k, int32_t order, int32_t* idx,
+                          int32_t* k_eff_host, void* hip_stream) {
+    return topk_impl(scores, score_stride, n_rows, n_groups, k, order, idx, k_eff_host, hip_stream, true);
+}
+
+static tom_status_t assemble_impl(const tom_oqm_t* h, int32_t layer0, int32_t n_layers,
+                                  const int32_t* idx, int32_t k, int32_t k_eff, int32_t prefix_rows,
+                                  const void* sys_k, const void* sys_v, void* k_out, void* v_out,
+                                  void* hip_stream, bool launch) {
     if (!h) return fail(TOM_ERR_INVALID_ARG, "handle is NULL");
     if (!h->bound) return fail(TOM_ERR_NOT_BOUND, "tom_oqm_bind has not been called");
     if (tom_status_t st = check_layers(h, layer0, n_layers)) return st;
     if (k < 1 || k_eff < 0 || k_eff > k)
         return fail(TOM_ERR_INVALID_ARG, "need k >= 1 and 0 <= k_eff <= k (k = %d, k_eff = %d)", k, k_eff);
-    if (k_eff == 0 || n_layers == 0) return TOM_OK;
-    if (!idx || !k_out || !v_out) return fail(TOM_ERR_INVALID_ARG, "idx, k_out and v_out must be non-NULL");
-    if (!aligned16(k_out) || !aligned16(v_out))
-        return fail(TOM_ERR_INVALID_ARG, "k_out and v_out must be 16-byte aligned");
+    if (prefix_rows < 0) return fail(TOM_ERR_INVALID_ARG, "prefix_rows < 0");
+    if ((sys_k == nullptr) != (sys_v == nullptr))
+        return fail(TOM_ERR_INVALID_ARG, "sys_k and sys_v must both be given or both be NULL");
+    const bool copy_prefix = prefix_rows > 0 && sys_k != nullptr;
+    if (n_layers == 0 || (k_eff == 0 && !copy_prefix)) return TOM_OK;
+    if (!k_out || !v_out) return fail(TOM_ERR_INVALID_ARG, "k_out and v_out must be non-NULL");
+    if (k_eff > 0 && !idx) return fail(TOM_ERR_INVALID_ARG, "idx must be non-NULL");
+    if (!aligned16(k_out) || !aligned16(v_out) || !aligned16(sys_k) || !aligned16(sys_v))
+        return fail(TOM_ERR_INVALID_ARG, "k_out, v_out, sys_k and sys_v must be 16-byte aligned");
     const tom_oqm_config_t& c = h->cfg;
     if (2 * c.n_kv_heads > 65535 || n_layers > 65535)
         return fail(TOM_ERR_UNSUPPORTED, "at most 32767 KV heads and 65535 layers per call");
+    if (!launch) return TOM_OK;
     DequantArgs a;
     a.codes = h->codes;
     a.meta = h->meta;
@@ -317,8 +343,53 @@ tom_status_t tom_oqm_dequant_gather(const tom_oqm_t* h, int32_t layer0, int32_t 
     a.k_eff = k_eff;
     a.n_groups = h->n_groups;
     a.qaxis = c.qaxis;
-    const hipError_t e = launch_dequant_gather(a, c.out_dtype, static_cast<hipStream_t>(hip_stream));
+    a.prefix_rows = prefix_rows;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    if (copy_prefix) {
+        const hipError_t e = launch_prefix_copy(a, sys_k, sys_v, c.out_dtype, s);
+        if (e != hipSuccess) return fail(TOM_ERR_HIP, "prefix copy launch: %s", hipGetErrorString(e));
+    }
+    const hipError_t e = launch_dequant_gather(a, c.out_dtype, s);
     if (e != hipSuccess) return fail(TOM_ERR_HIP, "dequant_gather launch: %s", hipGetErrorString(e));
+    return TOM_OK;
+}
+
+tom_status_t tom_oqm_dequant_gather(const tom_oqm_t* h, int32_t layer0, int32_t n_layers,
+                                    const int32_t* idx, int32_t k, int32_t k_eff, void* k_out,
+                                    void* v_out, void* hip_stream) {
+    return assemble_impl(h, layer0, n_layers, idx, k, k_eff, 0, nullptr, nullptr, k_out, v_out,
+                         hip_stream, true);
+}
+
+tom_status_t tom_oqm_assemble_active(const tom_oqm_t* h, int32_t layer0, int32_t n_layers,
+                                     const int32_t* idx, int32_t k, int32_t k_eff,
+                                     int32_t prefix_rows, const void* sys_k, const void* sys_v,
+                                     void* k_out, void* v_out, void* hip_stream) {
+    return assemble_impl(h, layer0, n_layers, idx, k, k_eff, prefix_rows, sys_k, sys_v, k_out, v_out,
+                         hip_stream, true);
+}
+
+tom_status_t tom_oqm_retrieve(const tom_oqm_t* h, int32_t layer0, int32_t n_layers, const void* q,
+                              int32_t q_dtype, int32_t t_q, int32_t k, int32_t path, float* scores,
+                              int64_t score_stride, int32_t* idx, int32_t prefix_rows,
+                              const void* sys_k, const void* sys_v, void* k_out, void* v_out,
+                              void* workspace, size_t workspace_bytes, int32_t* k_eff_host,
+                              void* hip_stream) {
+    if (!h) return fail(TOM_ERR_INVALID_ARG, "handle is NULL");
+    const int T = h->n_groups;
+    const int k_eff = k < T ? k : T;
+    for (int pass = 0; pass < 2; ++pass) {  // pass 0 validates all three steps, pass 1 launches them
+        const bool go = pass == 1;
+        if (tom_status_t st = score_impl(h, layer0, n_layers, q, q_dtype, t_q, scores, score_stride,
+                                         nullptr, path, workspace, workspace_bytes, hip_stream, go))
+            return st;
+        if (tom_status_t st = topk_impl(scores, score_stride, n_layers, T, k, TOM_ORDER_INDEX_ASC, idx,
+                                        k_eff_host, hip_stream, go))
+            return st;
+        if (tom_status_t st = assemble_impl(h, layer0, n_layers, idx, k, k_eff < 0 ? 0 : k_eff,
+                                            prefix_rows, sys_k, sys_v, k_out, v_out, hip_stream, go))
+            return st;
+    }
     return TOM_OK;
 }
 

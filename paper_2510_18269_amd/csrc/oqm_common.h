@@ -62,6 +62,7 @@ struct DequantArgs {
     int32_t n_kv_heads, head_dim, group_tokens, qgroup, capacity_groups;
     int32_t layer0, n_layers, k, k_eff, n_groups;
     int32_t qaxis;
+    int32_t prefix_rows;  // rows of each head's active buffer that precede the gathered groups
 };
 
 struct ScoreArgs {
@@ -81,6 +82,8 @@ struct ScoreArgs {
 hipError_t launch_quantize_append(const QuantArgs& a, int in_dtype, hipStream_t s);
 hipError_t launch_quantize_append_tokens(const QuantArgs& a, int in_dtype, hipStream_t s);
 hipError_t launch_dequant_gather(const DequantArgs& a, int out_dtype, hipStream_t s);
+hipError_t launch_prefix_copy(const DequantArgs& a, const void* sys_k, const void* sys_v, int out_dtype,
+                              hipStream_t s);
 hipError_t launch_query_fold(const ScoreArgs& a, bool want_tokens, hipStream_t s);
 hipError_t launch_score_mean_query(const ScoreArgs& a, hipStream_t s);
 hipError_t launch_score_token_gemm(const ScoreArgs& a, hipStream_t s);

@@ -48,8 +48,9 @@ __global__ void __launch_bounds__(kBlock) dequant_gather_kernel(const DequantArg
 #pragma unroll
         for (int i = 0; i < 8; ++i) ch[i] = meta_t[slot * 8 + i];
     }
+    const int64_t head_rows = (int64_t)a.prefix_rows + (int64_t)a.k * G;  // rows per head buffer
     char* out = static_cast<char*>(kv ? a.v_out : a.k_out) +
-                ((((int64_t)li * H + h) * a.k + r) * G) * (int64_t)d * EB;
+                (((int64_t)li * H + h) * head_rows + a.prefix_rows + (int64_t)r * G) * (int64_t)d * EB;
     // offsets inside one tile fit 32 bits (G * d * 4 < 2^31 is checked on the host)
     const uint32_t code_lane = ((uint32_t)row0 * lpr + slot) * 4u;
     const int meta_lane = TOKEN_AXIS ? 0 : row0 * ng + slot / lpg;
@@ -85,6 +86,19 @@ __global__ void __launch_bounds__(kBlock) dequant_gather_kernel(const DequantArg
     }
 }
 
+// System-token prefix (the part of the paper's dual-structure memory that stays in 16 bits):
+// rows [0, prefix_rows) of every head's active buffer are copied from
+// sys [n_layers][H_k][prefix_rows][d].  grid (chunks, H_k * n_layers, 2), 16 bytes per lane.
+__global__ void __launch_bounds__(kBlock) prefix_copy_kernel(const DequantArgs a, const char* sys_k,
+                                                             const char* sys_v, const int64_t head_bytes,
+                                                             const int64_t prefix_bytes) {
+    const int64_t off = ((int64_t)blockIdx.x * kBlock + threadIdx.x) * 16;
+    if (off >= prefix_bytes) return;
+    const char* src = (blockIdx.z ? sys_v : sys_k) + (int64_t)blockIdx.y * prefix_bytes + off;
+    char* dst = static_cast<char*>(blockIdx.z ? a.v_out : a.k_out) + (int64_t)blockIdx.y * head_bytes + off;
+    *reinterpret_cast<u32x4*>(dst) = *reinterpret_cast<const u32x4*>(src);
+}
+
 template <typename OUT>
 hipError_t launch_t(const DequantArgs& a, hipStream_t s) {
     if (a.n_layers == 0 || a.k_eff == 0) return hipSuccess;
@@ -108,7 +122,21 @@ hipError_t launch_t(const DequantArgs& a, hipStream_t s) {
 
 }  // namespace
 
+hipError_t launch_prefix_copy(const DequantArgs& a, const void* sys_k, const void* sys_v, int out_dtype,
+                              hipStream_t s) {
+    const int64_t eb = out_dtype == TOM_F32 ? 4 : 2;
+    const int64_t prefix_bytes = (int64_t)a.prefix_rows * a.head_dim * eb;  // multiple of 16: d % 8 == 0
+    const int64_t head_bytes = ((int64_t)a.prefix_rows + (int64_t)a.k * a.group_tokens) * a.head_dim * eb;
+    if (prefix_bytes == 0 || a.n_layers == 0) return hipSuccess;
+    const int64_t chunks = (prefix_bytes / 16 + kBlock - 1) / kBlock;
+    if (chunks > 0x7fffffffLL || (int64_t)a.n_kv_heads * a.n_layers > 65535) return hipErrorInvalidValue;
+    prefix_copy_kernel<<<dim3((unsigned)chunks, a.n_kv_heads * a.n_layers, 2), dim3(kBlock), 0, s>>>(
+        a, static_cast<const char*>(sys_k), static_cast<const char*>(sys_v), head_bytes, prefix_bytes);
+    return hipGetLastError();
+}
+
 hipError_t launch_dequant_gather(const DequantArgs& a, int out_dtype, hipStream_t s) {
+    if (a.k_eff == 0) return hipSuccess;
     switch (out_dtype) {
         case TOM_F32: return launch_t<In_f32>(a, s);
         case TOM_BF16: return launch_t<In_bf16>(a, s);

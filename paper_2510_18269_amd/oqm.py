@@ -30,7 +30,8 @@ _STATUS_NAMES = ["TOM_OK", "TOM_ERR_INVALID_ARG", "TOM_ERR_CAPACITY", "TOM_ERR_U
 EXPORTS = ["tom_oqm_query_sizes", "tom_oqm_create", "tom_oqm_bind", "tom_oqm_reset",
            "tom_oqm_num_groups", "tom_oqm_set_num_groups", "tom_oqm_destroy", "tom_last_error",
            "tom_oqm_k_from_budget", "tom_oqm_quantize_append", "tom_oqm_score_workspace_bytes",
-           "tom_oqm_score_groups", "tom_oqm_topk", "tom_oqm_dequant_gather"]
+           "tom_oqm_score_groups", "tom_oqm_topk", "tom_oqm_dequant_gather",
+           "tom_oqm_assemble_active", "tom_oqm_retrieve"]
 
 
 class TomError(RuntimeError):
@@ -76,6 +77,9 @@ def _load():
                                        C.c_size_t, vp]
     L.tom_oqm_topk.argtypes = [vp, i64, i32, i32, i32, i32, vp, C.POINTER(i32), vp]
     L.tom_oqm_dequant_gather.argtypes = [vp, i32, i32, vp, i32, i32, vp, vp, vp]
+    L.tom_oqm_assemble_active.argtypes = [vp, i32, i32, vp, i32, i32, i32, vp, vp, vp, vp, vp]
+    L.tom_oqm_retrieve.argtypes = [vp, i32, i32, vp, i32, i32, i32, i32, vp, i64, vp, i32, vp, vp,
+                                   vp, vp, vp, C.c_size_t, C.POINTER(i32), vp]
     for name in EXPORTS:
         fn = getattr(L, name)
         if name not in ("tom_oqm_destroy", "tom_last_error", "tom_oqm_score_workspace_bytes"):
@@ -200,6 +204,29 @@ def tom_oqm_dequant_gather(h: int, layer0: int, n_layers: int, idx, k: int, k_ef
                            v_out, stream=None) -> None:
     _check(lib.tom_oqm_dequant_gather(h, layer0, n_layers, _ptr(idx), k, k_eff, _ptr(k_out),
                                       _ptr(v_out), _stream(stream)))
+
+
+def tom_oqm_assemble_active(h: int, layer0: int, n_layers: int, idx, k: int, k_eff: int,
+                            prefix_rows: int, sys_k, sys_v, k_out, v_out, stream=None) -> None:
+    _check(lib.tom_oqm_assemble_active(h, layer0, n_layers, _ptr(idx), k, k_eff, prefix_rows,
+                                       _ptr(sys_k), _ptr(sys_v), _ptr(k_out), _ptr(v_out),
+                                       _stream(stream)))
+
+
+def tom_oqm_retrieve(h: int, layer0: int, n_layers: int, q, t_q: int, k: int, scores,
+                     score_stride: int, idx, k_out, v_out, workspace, path: int = TOM_SCORE_AUTO,
+                     prefix_rows: int = 0, sys_k=None, sys_v=None, stream=None,
+                     q_dtype: int | None = None) -> int:
+    """score -> top-k -> assemble in one call.  Returns k_eff."""
+    if q_dtype is None:
+        q_dtype = _DTYPE_OF_TORCH[q.dtype]
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    k_eff = C.c_int32(-1)
+    _check(lib.tom_oqm_retrieve(h, layer0, n_layers, _ptr(q), q_dtype, t_q, k, path, _ptr(scores),
+                                score_stride, _ptr(idx), prefix_rows, _ptr(sys_k), _ptr(sys_v),
+                                _ptr(k_out), _ptr(v_out), _ptr(workspace), ws_bytes,
+                                C.byref(k_eff), _stream(stream)))
+    return k_eff.value
 
 
 # --------------------------------------------------------------------------- convenience

@@ -108,6 +108,44 @@ def test_host_side_validation_before_any_launch(oqm):
         oqm.tom_oqm_destroy(h)
 
 
+def test_assemble_and_retrieve_validation(oqm):
+    cfg = oqm.make_config(2, 2, 4, 64, 16, 32, 8)
+    h = oqm.tom_oqm_create(cfg)
+    try:
+        fake = 0x1000
+        oqm.tom_oqm_bind(h, fake, fake, fake)
+        with pytest.raises(oqm.TomError) as e:           # negative prefix
+            oqm.tom_oqm_assemble_active(h, 0, 2, fake, 4, 1, -1, None, None, fake, fake)
+        assert e.value.status == oqm.TOM_ERR_INVALID_ARG
+        with pytest.raises(oqm.TomError) as e:           # only one system tensor
+            oqm.tom_oqm_assemble_active(h, 0, 2, fake, 4, 1, 3, fake, None, fake, fake)
+        assert e.value.status == oqm.TOM_ERR_INVALID_ARG
+        with pytest.raises(oqm.TomError) as e:           # misaligned system tensor
+            oqm.tom_oqm_assemble_active(h, 0, 2, fake, 4, 1, 3, fake + 2, fake, fake, fake)
+        assert e.value.status == oqm.TOM_ERR_INVALID_ARG
+        # nothing to do: no groups selected and no prefix to copy
+        oqm.tom_oqm_assemble_active(h, 0, 2, fake, 4, 0, 3, None, None, fake, fake)
+        # one-call retrieval on an empty store: k_eff = 0, nothing launched
+        assert oqm.tom_oqm_retrieve(h, 0, 2, fake, 1, 4, fake, 8, fake, fake, fake, None,
+                                    q_dtype=oqm.TOM_F32) == 0
+        # with groups stored, every step is validated before the first launch:
+        # the gather's k_out is missing, so the score kernel must not have been queued
+        oqm.tom_oqm_set_num_groups(h, 8)
+        nbytes = oqm.tom_oqm_score_workspace_bytes(h, 2, 1, oqm.TOM_SCORE_AUTO)
+
+        class FakeWs:                                    # a workspace that is never touched
+            is_cuda = True
+            def data_ptr(self): return fake
+            def numel(self): return nbytes
+            def element_size(self): return 1
+        with pytest.raises(oqm.TomError) as e:
+            oqm.tom_oqm_retrieve(h, 0, 2, fake, 1, 4, fake, 8, fake, None, fake, FakeWs(),
+                                 q_dtype=oqm.TOM_F32)
+        assert e.value.status == oqm.TOM_ERR_INVALID_ARG and "k_out" in str(e.value)
+    finally:
+        oqm.tom_oqm_destroy(h)
+
+
 def test_token_axis_sizes(oqm):
     cfg = oqm.make_config(28, 4, 28, 128, 50, 64, 100, qaxis=oqm.TOM_QAXIS_TOKENS)
     cfg.qgroup = 7                                        # ignored on the token axis

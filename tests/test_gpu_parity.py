@@ -263,6 +263,67 @@ def test_both_score_paths_agree(oqm):
         mem.close()
 
 
+@pytest.mark.parametrize("qaxis,G,prefix,dt", [(0, 196, 14, "bf16"), (0, 50, 1, "f16"), (1, 50, 14, "f16"),
+                                               (0, 13, 0, "f32")])
+def test_assemble_with_system_prefix_and_one_call_retrieve(oqm, qaxis, G, prefix, dt):
+    """System-token rows in front of the gathered groups (dual-structure memory), and the
+    one-call score -> top-k -> assemble path; both against the oracle's step-by-step result."""
+    w = synth_kv.Workload("X", 3, 4, 28, 128, G, 45, 64, 24, 7, dt, "cosine", 500 + G, "layer_std", 45)
+    st, mem = H.pair_for(oqm, w, qaxis=qaxis)
+    try:
+        kk, vv = synth_kv.kv_frames(w, 0, w.n_frames)
+        H.append_both(oqm, st, mem, kk, vv)
+        q = synth_kv.query(w)
+        cfg = st.cfg
+        L, Hk, d, k = w.n_layers, w.n_kv_heads, w.head_dim, w.top_k
+        tdt = mem.out_torch_dtype()
+        g = torch.Generator().manual_seed(77)
+        sys_k = torch.randn(L, Hk, max(prefix, 1), d, generator=g).to(tdt)[:, :, :prefix].contiguous()
+        sys_v = torch.randn(L, Hk, max(prefix, 1), d, generator=g).to(tdt)[:, :, :prefix].contiguous()
+        # oracle, step by step
+        ref_scores = H.orc.score_groups(st, H.bits(q), H.DT[dt][0])
+        ref_idx, k_eff = H.orc.topk(ref_scores, k)
+        fill = 0x7FC1 if dt != "f32" else None
+        ref_k, ref_v = H.orc.assemble_active(st, ref_idx, k_eff, prefix, H.bits(sys_k) if prefix else None,
+                                             H.bits(sys_v) if prefix else None, fill=fill)
+        # GPU: one call
+        rows = prefix + k * G
+        ko = torch.zeros((L, Hk, rows, d), dtype=tdt, device="cuda")
+        vo = torch.zeros((L, Hk, rows, d), dtype=tdt, device="cuda")
+        if fill is not None:
+            ko.view(torch.int16).fill_(fill)
+            vo.view(torch.int16).fill_(fill)
+        scores = torch.empty((L, w.n_frames + 3), dtype=torch.float32, device="cuda")
+        idx = torch.full((L, k), -7, dtype=torch.int32, device="cuda")
+        ws = torch.empty(oqm.tom_oqm_score_workspace_bytes(mem.handle, L, w.t_q, oqm.TOM_SCORE_AUTO, False),
+                         dtype=torch.uint8, device="cuda")
+        got_keff = oqm.tom_oqm_retrieve(mem.handle, 0, L, q.cuda(), w.t_q, k, scores, scores.shape[1], idx,
+                                        ko, vo, ws, prefix_rows=prefix,
+                                        sys_k=sys_k.cuda() if prefix else None,
+                                        sys_v=sys_v.cuda() if prefix else None)
+        torch.cuda.synchronize()
+        assert got_keff == k_eff == k
+        sc = scores.cpu().numpy()[:, :w.n_frames]
+        assert np.all(np.abs(sc.astype(np.float64) - ref_scores) <= H.score_bound(st, q, ref_scores))
+        assert np.array_equal(idx.cpu().numpy(), ref_idx)
+        assert np.array_equal(H.bits(ko), ref_k) and np.array_equal(H.bits(vo), ref_v)
+        # GPU: the assemble step alone, prefix left untouched when no system tensors are given
+        ko2 = torch.zeros_like(ko)
+        vo2 = torch.zeros_like(vo)
+        oqm.tom_oqm_assemble_active(mem.handle, 0, L, idx, k, k_eff - 2, prefix, None, None, ko2, vo2)
+        torch.cuda.synchronize()
+        b = H.bits(ko2)
+        assert np.all(b[:, :, :prefix] == 0) and np.all(b[:, :, prefix + (k_eff - 2) * G:] == 0)
+        assert np.array_equal(b[:, :, prefix:prefix + (k_eff - 2) * G], ref_k[:, :, prefix:prefix + (k_eff - 2) * G])
+        # prefix only (nothing retrieved yet)
+        if prefix:
+            oqm.tom_oqm_assemble_active(mem.handle, 0, L, None, k, 0, prefix, sys_k.cuda(), sys_v.cuda(), ko2, vo2)
+            torch.cuda.synchronize()
+            assert np.array_equal(H.bits(vo2)[:, :, :prefix], H.bits(sys_v))
+    finally:
+        mem.close()
+
+
 def test_division_shortcuts_are_exact_for_every_input():
     """The quantize kernel computes (max - min) / 15 and 1 / s with one FMA correction step
     instead of the full IEEE division sequence; the library's self-check program compares

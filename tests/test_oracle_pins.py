@@ -522,6 +522,31 @@ def test_gather_rejects_bad_index(oracle):
         oracle.dequant_gather(st, np.array([[0, 5], [0, 1]], np.int32), 2)   # 5 >= n_groups
 
 
+def test_assemble_places_system_prefix_then_groups(oracle):
+    """Dual-structure memory: the active buffer of every (layer, head) is the 16-bit system
+    rows, bit for bit, followed by exactly what the plain gather produces."""
+    cfg = _small_cfg(oracle, out_dtype=oracle.BF16)
+    st = oracle.new_store(cfg)
+    r = _rng(56)
+    k = r.standard_normal((6, 2, 2, 5, 32)).astype(np.float32)
+    oracle.quantize_append(st, k, -k)
+    idx = np.array([[0, 3, 5, -1], [1, 2, 4, -1]], np.int32)
+    G, P = 5, 3
+    plain_k, plain_v = oracle.dequant_gather(st, idx, 3, fill=0x7FC0)
+    sys_k = r.integers(0, 2 ** 16, (2, 2, P, 32)).astype(np.uint16)
+    sys_v = r.integers(0, 2 ** 16, (2, 2, P, 32)).astype(np.uint16)
+    ko, vo = oracle.assemble_active(st, idx, 3, P, sys_k, sys_v, fill=0x7FC0)
+    assert ko.shape == (2, 2, P + 4 * G, 32)
+    assert np.array_equal(ko[:, :, :P], sys_k) and np.array_equal(vo[:, :, :P], sys_v)
+    assert np.array_equal(ko[:, :, P:], plain_k) and np.array_equal(vo[:, :, P:], plain_v)
+    # no system tensors: the prefix rows are left as they were
+    ko, vo = oracle.assemble_active(st, idx, 3, P, None, None, fill=0x1234)
+    assert np.all(ko[:, :, :P] == 0x1234) and np.array_equal(ko[:, :, P:P + 3 * G], plain_k[:, :, :3 * G])
+    # prefix of zero rows is the plain gather
+    ko, vo = oracle.assemble_active(st, idx, 3, 0, None, None, fill=0x7FC0)
+    assert np.array_equal(ko, plain_k) and np.array_equal(vo, plain_v)
+
+
 # --------------------------------------------------------------------------- whole path, C1
 def test_tiny_stream_end_to_end_brute_force(oracle):
     """The smallest benchmark configuration, every step re-derived with numpy/torch."""
