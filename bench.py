@@ -26,15 +26,15 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 METRIC = "OQM quantize-append + retrieve/dequant HBM GB/s (% of peak); retrieval ms/query"
 
 
-def bytes_append(w, n_frames, in_bytes):
+def bytes_append(w, n_frames, in_bytes, bits=4):
     e = n_frames * w.n_layers * 2 * w.n_kv_heads * w.group_tokens * w.head_dim
     keys = n_frames * w.n_layers * w.n_kv_heads * w.head_dim * 4
-    return e * in_bytes + e // 2 + (e // w.qgroup) * 8 + keys, e
+    return e * in_bytes + e * bits // 8 + (e // w.qgroup) * 8 + keys, e
 
 
-def bytes_gather(w, k_eff, out_bytes):
+def bytes_gather(w, k_eff, out_bytes, bits=4):
     e = w.n_layers * k_eff * 2 * w.n_kv_heads * w.group_tokens * w.head_dim
-    return e // 2 + (e // w.qgroup) * 8 + e * out_bytes + w.n_layers * k_eff * 4, e
+    return e * bits // 8 + (e // w.qgroup) * 8 + e * out_bytes + w.n_layers * k_eff * 4, e
 
 
 def bytes_score(w, T, q_bytes):
@@ -61,7 +61,7 @@ def measured_traffic(kernel, workload):
     return None
 
 
-def cpu_baseline(w, batches_cpu, q_cpu, threads, qaxis=0):
+def cpu_baseline(w, batches_cpu, q_cpu, threads, qaxis=0, bits=4):
     """The oracle, as it stands, on a bounded sample of the same workload: the given append
     batches (all layers) and one retrieval over what they stored.  Threads split layers."""
     from concurrent.futures import ThreadPoolExecutor
@@ -74,7 +74,7 @@ def cpu_baseline(w, batches_cpu, q_cpu, threads, qaxis=0):
     dt = {"f32": 0, "bf16": 1, "f16": 2}[w.dtype]
     F = sum(b[0].shape[0] for b in batches_cpu)
     cfg = orc.make_config(w.n_layers, w.n_kv_heads, w.n_q_heads, w.head_dim, w.group_tokens,
-                          w.qgroup, F, qaxis=qaxis, in_dtype=dt, out_dtype=dt,
+                          w.qgroup, F, qaxis=qaxis, bits=bits, in_dtype=dt, out_dtype=dt,
                           sim=1 if w.sim == "cosine" else 0)
     st = orc.new_store(cfg)
     L = w.n_layers
@@ -110,8 +110,8 @@ def cpu_baseline(w, batches_cpu, q_cpu, threads, qaxis=0):
         list(ex.map(layer_job, range(L)))
     dtm = time.perf_counter() - t0
     eb = 4 if w.dtype == "f32" else 2
-    ba, ea = bytes_append(w, F, eb)
-    bg, eg = bytes_gather(w, k_eff, eb)
+    ba, ea = bytes_append(w, F, eb, bits)
+    bg, eg = bytes_gather(w, k_eff, eb, bits)
     total = ba + bg + bytes_score(w, F, eb) + bytes_topk(w, F, k_eff)
     return {"value": total / dtm / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
             "sample": f"{F} frames x {L} layers appended ({len(kb)} calls) + 1 query "
@@ -130,6 +130,7 @@ def main():
     ap.add_argument("--qaxis", default="head_dim", choices=["head_dim", "tokens"],
                     help="tokens = the paper's Eq. 9 (scale/zero per channel over the G tokens)")
     ap.add_argument("--group-tokens", type=int, default=0, help="override G (the paper keeps 50)")
+    ap.add_argument("--bits", type=int, default=4, choices=[4, 2], help="code width (2 = the paper's ablation)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-batches", type=int, default=12)
     args = ap.parse_args()
@@ -157,7 +158,7 @@ def main():
     dtc = {"f32": oqm.TOM_F32, "bf16": oqm.TOM_BF16, "f16": oqm.TOM_F16}[w.dtype]
     cfg = oqm.make_config(w.n_layers, w.n_kv_heads, w.n_q_heads, w.head_dim, w.group_tokens,
                           w.qgroup, T, qaxis=oqm.TOM_QAXIS_TOKENS if tok else oqm.TOM_QAXIS_HEAD_DIM,
-                          in_dtype=dtc, out_dtype=dtc,
+                          bits=args.bits, in_dtype=dtc, out_dtype=dtc,
                           sim=oqm.TOM_SIM_COSINE if w.sim == "cosine" else oqm.TOM_SIM_DOT)
     mem = oqm.Memory.allocate(cfg, dev)
     if tok:   # byte model: one (scale, zero) pair per channel and tile instead of per gs elements
@@ -165,7 +166,7 @@ def main():
     L = w.n_layers
 
     # distinct input batches, more than the 256 MB last-level cache can hold, rotated per step
-    batch_bytes = bytes_append(w, fpa, eb)[0]
+    batch_bytes = bytes_append(w, fpa, eb, args.bits)[0]
     n_batches = max(2, min(T // fpa, int(3.0e9 // max(batch_bytes, 1)) or 1, 64))
     batches = [synth_kv.kv_frames(w, i * fpa, fpa, dev) for i in range(n_batches)]
     queries = [synth_kv.query(w, i, dev) for i in range(4)]
@@ -240,8 +241,9 @@ def main():
 
     ms_append, ms_score, ms_topk, ms_gather = avg_ms(0, 1), avg_ms(1, 2), avg_ms(2, 3), avg_ms(3, 4)
     ms_step = wall * 1e3 / args.steps
-    b_app, e_app = bytes_append(w, fpa, eb)
-    b_gat, e_gat = bytes_gather(w, k_eff, eb)
+    b_app, e_app = bytes_append(w, fpa, eb, args.bits)
+    b_gat, e_gat = bytes_gather(w, k_eff, eb, args.bits)
+    default_variant = not tok and args.bits == 4 and not args.group_tokens and not args.frames_per_append
     b_sc, b_tk = bytes_score(w, T, eb), bytes_topk(w, T, k_eff)
     total_bytes = b_app + b_gat + b_sc + b_tk
     gbps = lambda b, ms: b / (ms * 1e-3) / 1e9
@@ -258,7 +260,7 @@ def main():
         "config": {
             "workload": f"{w.name}: {L} layers, {w.n_kv_heads} KV heads ({w.n_q_heads} query heads), "
                         f"head_dim {w.head_dim}, {w.dtype} K/V, {T} frames x {w.group_tokens} tokens stored, "
-                        f"{fpa} frames per quantize-append, 4-bit codes, "
+                        f"{fpa} frames per quantize-append, {args.bits}-bit codes, "
                         + (f"scale/zero per channel over the {w.group_tokens} tokens, " if tok else
                            f"quant-group {w.qgroup} over head_dim, ") +
                         ""
@@ -280,12 +282,12 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "dequant_gather_kernel",
                      "achieved": round(gbps(b_gat, ms_gather), 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(gbps(b_gat, ms_gather) / HBM_PEAK_GBPS, 4),
-                     "traffic": measured_traffic("dequant_gather_kernel", w.name),
+                     "traffic": measured_traffic("dequant_gather_kernel", w.name) if default_variant else None,
                      "algorithmic_bytes": b_gat, "avg_launch_us": round(ms_gather * 1e3, 2)},
         "roofline_append": {"bound": "hbm", "kernel": "quantize_append_kernel",
                             "achieved": round(gbps(b_app, ms_append), 1), "peak": HBM_PEAK_GBPS,
                             "unit": "GB/s", "frac": round(gbps(b_app, ms_append) / HBM_PEAK_GBPS, 4),
-                            "traffic": measured_traffic("quantize_append_kernel", w.name),
+                            "traffic": measured_traffic("quantize_append_kernel", w.name) if default_variant else None,
                             "algorithmic_bytes": b_app, "avg_launch_us": round(ms_append * 1e3, 2)},
     }
 
@@ -294,7 +296,7 @@ def main():
         host = [(k.cpu(), v.cpu()) for k, v in batches[:min(nb, n_batches)]]
         sample = [host[i % len(host)] for i in range(nb)]      # cycle the resident batches
         threads = min(16, os.cpu_count() or 1)
-        out["cpu_baseline"] = cpu_baseline(w, sample, queries[0].cpu(), threads, 1 if tok else 0)
+        out["cpu_baseline"] = cpu_baseline(w, sample, queries[0].cpu(), threads, 1 if tok else 0, args.bits)
         out["cpu_baseline"]["value"] = round(out["cpu_baseline"]["value"], 3)
         del out["cpu_baseline"]["tokens_per_s_append"]
     print(json.dumps(out))

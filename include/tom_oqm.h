@@ -92,7 +92,7 @@ typedef struct {
     int32_t qgroup;          /* gs in {8, 16, 32, 64, 128}, divides d (HEAD_DIM axis);
                                 ignored on the TOKENS axis                               */
     int32_t qaxis;           /* tom_qaxis_t                                              */
-    int32_t bits;            /* 4                                                        */
+    int32_t bits;            /* 4 (paper default) or 2 (the paper's bit-width ablation)  */
     int32_t capacity_groups; /* T_cap: frame-groups the bound storage can hold           */
     int32_t in_dtype;        /* tom_dtype_t of K/V handed to quantize_append             */
     int32_t out_dtype;       /* tom_dtype_t of the active KV buffer                      */

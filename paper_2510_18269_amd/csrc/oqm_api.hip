@@ -41,10 +41,7 @@ static tom_status_t check_config(const tom_oqm_config_t* c) {
         return fail(TOM_ERR_INVALID_ARG, "in_dtype / out_dtype must be TOM_F32, TOM_BF16 or TOM_F16");
     if (c->sim != TOM_SIM_DOT && c->sim != TOM_SIM_COSINE)
         return fail(TOM_ERR_INVALID_ARG, "sim must be TOM_SIM_DOT or TOM_SIM_COSINE");
-    if (c->bits != 4) {
-        if (c->bits == 2) return fail(TOM_ERR_UNSUPPORTED, "2-bit codes are not built yet");
-        return fail(TOM_ERR_INVALID_ARG, "bits must be 4");
-    }
+    if (c->bits != 4 && c->bits != 2) return fail(TOM_ERR_INVALID_ARG, "bits must be 4 or 2");
     if (c->qaxis != TOM_QAXIS_HEAD_DIM && c->qaxis != TOM_QAXIS_TOKENS)
         return fail(TOM_ERR_INVALID_ARG, "qaxis is not a tom_qaxis_t");
     if (c->qaxis == TOM_QAXIS_HEAD_DIM) {
@@ -185,6 +182,7 @@ tom_status_t tom_oqm_quantize_append(tom_oqm_t* h, int32_t layer0, int32_t n_lay
     a.n_frames = n_frames;
     a.first_group = h->n_groups;
     a.qaxis = c.qaxis;
+    a.bits = c.bits;
     const hipError_t e = launch_quantize_append(a, c.in_dtype, static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return fail(TOM_ERR_HIP, "quantize_append launch: %s", hipGetErrorString(e));
     if (commit) h->n_groups += n_frames;
@@ -343,6 +341,7 @@ static tom_status_t assemble_impl(const tom_oqm_t* h, int32_t layer0, int32_t n_
     a.k_eff = k_eff;
     a.n_groups = h->n_groups;
     a.qaxis = c.qaxis;
+    a.bits = c.bits;
     a.prefix_rows = prefix_rows;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     if (copy_prefix) {

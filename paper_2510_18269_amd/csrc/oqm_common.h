@@ -51,6 +51,7 @@ struct QuantArgs {
     int32_t n_kv_heads, head_dim, group_tokens, qgroup, capacity_groups;
     int32_t layer0, n_layers, n_frames, first_group;
     int32_t qaxis;
+    int32_t bits;  // 4 or 2
 };
 
 struct DequantArgs {
@@ -62,6 +63,7 @@ struct DequantArgs {
     int32_t n_kv_heads, head_dim, group_tokens, qgroup, capacity_groups;
     int32_t layer0, n_layers, k, k_eff, n_groups;
     int32_t qaxis;
+    int32_t bits;         // 4 or 2
     int32_t prefix_rows;  // rows of each head's active buffer that precede the gathered groups
 };
 

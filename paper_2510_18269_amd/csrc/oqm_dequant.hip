@@ -10,6 +10,8 @@
 // word of codes (8 channels) into one 128-bit non-temporal store, so each store
 // instruction of a wave writes 1 KB of contiguous bf16.  HBM-bound: 0.5 + 8/gs
 // bytes read and 2 bytes written per element.
+#include <type_traits>
+
 #include "oqm_common.h"
 #include "oqm_device.h"
 
@@ -18,9 +20,11 @@ namespace {
 
 // kUnroll: rows per lane whose loads are issued before any is converted; the host picks it
 // so that a whole tile is covered in one trip when it fits (13 trips of 16 rows for 196 x 128).
-template <typename OUT, int kUnroll, bool TOKEN_AXIS>
+template <typename OUT, int kUnroll, bool TOKEN_AXIS, int BITS>
 __global__ void __launch_bounds__(kBlock) dequant_gather_kernel(const DequantArgs a, const int lpg) {
     constexpr int EB = elem_bytes<OUT>::value;
+    constexpr uint32_t CW = BITS;          // bytes of packed codes per lane and row (8 channels)
+    constexpr uint32_t CMASK = (1u << BITS) - 1u;
     const int H = a.n_kv_heads, d = a.head_dim, G = a.group_tokens;
     const int r = blockIdx.x;
     const int kv = blockIdx.y & 1;
@@ -39,7 +43,7 @@ __global__ void __launch_bounds__(kBlock) dequant_gather_kernel(const DequantArg
     const int ng = TOKEN_AXIS ? 0 : lpr / lpg;
 
     const int64_t tile = (((int64_t)(a.layer0 + li) * 2 + kv) * a.capacity_groups + t) * H + h;
-    const char* codes_t = reinterpret_cast<const char*>(a.codes + tile * ((int64_t)G * d / 2));
+    const char* codes_t = reinterpret_cast<const char*>(a.codes + tile * ((int64_t)G * d * BITS / 8));
     // token axis (Eq. 9): one pair per channel, d pairs per tile; else G * d/gs pairs
     const f32x2* meta_t =
         reinterpret_cast<const f32x2*>(a.meta) + tile * (TOKEN_AXIS ? (int64_t)d : (int64_t)G * ng);
@@ -52,7 +56,7 @@ __global__ void __launch_bounds__(kBlock) dequant_gather_kernel(const DequantArg
     char* out = static_cast<char*>(kv ? a.v_out : a.k_out) +
                 (((int64_t)li * H + h) * head_rows + a.prefix_rows + (int64_t)r * G) * (int64_t)d * EB;
     // offsets inside one tile fit 32 bits (G * d * 4 < 2^31 is checked on the host)
-    const uint32_t code_lane = ((uint32_t)row0 * lpr + slot) * 4u;
+    const uint32_t code_lane = ((uint32_t)row0 * lpr + slot) * CW;
     const int meta_lane = TOKEN_AXIS ? 0 : row0 * ng + slot / lpg;
     const uint32_t out_lane = ((uint32_t)row0 * d + slot * 8u) * EB;
 
@@ -65,7 +69,7 @@ __global__ void __launch_bounds__(kBlock) dequant_gather_kernel(const DequantArg
             w[u] = 0u;
             sm[u] = f32x2{0.0f, 0.0f};
             if (rb + row0 < G) {
-                w[u] = *reinterpret_cast<const uint32_t*>(codes_t + (code_lane + (uint32_t)rb * lpr * 4u));
+                w[u] = load_codes8<BITS>(codes_t + (code_lane + (uint32_t)rb * lpr * CW));
                 if (!TOKEN_AXIS) sm[u] = meta_t[meta_lane + rb * ng];
             }
         }
@@ -76,7 +80,7 @@ __global__ void __launch_bounds__(kBlock) dequant_gather_kernel(const DequantArg
                 float x[8];
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
-                    const float c = (float)((w[u] >> (4 * i)) & 15u);
+                    const float c = (float)((w[u] >> (BITS * i)) & CMASK);
                     const f32x2 p = TOKEN_AXIS ? ch[i] : sm[u];
                     x[i] = __builtin_fmaf(c, p[0], p[1]);  // Eq. 11, rounded once to float32
                 }
@@ -107,16 +111,18 @@ hipError_t launch_t(const DequantArgs& a, hipStream_t s) {
     const int trips = (a.group_tokens + rpp - 1) / rpp;  // row passes per tile
     const int lpg = a.qgroup / 8;  // unused for the token axis
     const bool tok = a.qaxis == TOM_QAXIS_TOKENS;
-    if (trips <= 4) {
-        if (tok) dequant_gather_kernel<OUT, 4, true><<<grid, block, 0, s>>>(a, 1);
-        else dequant_gather_kernel<OUT, 4, false><<<grid, block, 0, s>>>(a, lpg);
-    } else if (trips <= 8 || trips > 13) {
-        if (tok) dequant_gather_kernel<OUT, 8, true><<<grid, block, 0, s>>>(a, 1);
-        else dequant_gather_kernel<OUT, 8, false><<<grid, block, 0, s>>>(a, lpg);
-    } else {
-        if (tok) dequant_gather_kernel<OUT, 13, true><<<grid, block, 0, s>>>(a, 1);
-        else dequant_gather_kernel<OUT, 13, false><<<grid, block, 0, s>>>(a, lpg);
-    }
+    auto go = [&](auto unroll, auto bits) {
+        constexpr int U = decltype(unroll)::value, B = decltype(bits)::value;
+        if (tok) dequant_gather_kernel<OUT, U, true, B><<<grid, block, 0, s>>>(a, 1);
+        else dequant_gather_kernel<OUT, U, false, B><<<grid, block, 0, s>>>(a, lpg);
+    };
+    auto with_bits = [&](auto unroll) {
+        if (a.bits == 2) go(unroll, std::integral_constant<int, 2>{});
+        else go(unroll, std::integral_constant<int, 4>{});
+    };
+    if (trips <= 4) with_bits(std::integral_constant<int, 4>{});
+    else if (trips <= 8 || trips > 13) with_bits(std::integral_constant<int, 8>{});
+    else with_bits(std::integral_constant<int, 13>{});
     return hipGetLastError();
 }
 

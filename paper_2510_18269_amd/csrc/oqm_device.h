@@ -140,6 +140,19 @@ __device__ __forceinline__ float div15_exact(float a) {
     const float e = __builtin_fmaf(-15.0f, q, a);
     return __builtin_fmaf(e, c, q);
 }
+// a / 3 (2-bit codes have 3 steps) by the same construction; checked the same way.
+__device__ __forceinline__ float div3_exact(float a) {
+    const float c = 1.0f / 3.0f;
+    const float q = __fmul_rn(a, c);
+    const float e = __builtin_fmaf(-3.0f, q, a);
+    return __builtin_fmaf(e, c, q);
+}
+// (max - min) / (2^BITS - 1)
+template <int BITS>
+__device__ __forceinline__ float div_levels_exact(float a) {
+    if constexpr (BITS == 4) return div15_exact(a);
+    else return div3_exact(a);
+}
 __device__ __forceinline__ float rcp_exact(float s) {
     const float r = __builtin_amdgcn_rcpf(s);
     const float e = __builtin_fmaf(-s, r, 1.0f);
@@ -163,6 +176,39 @@ __device__ __forceinline__ uint32_t pack8(const float (&t)[8]) {
     return __builtin_amdgcn_perm(hi, lo, 0x05040100u);  // {lo.b0, lo.b1, hi.b0, hi.b1}
 }
 
+
+// 2-bit codes: channel u of the lane's 8 in bits [2u, 2u + 2) of a 16-bit word.  The
+// exponent bits 0x4B000000 of every t stay at or above bit 24 under the left shifts.
+__device__ __forceinline__ uint32_t pack8_2bit(const float (&t)[8]) {
+    uint32_t w = __float_as_uint(t[0]);
+#pragma unroll
+    for (int i = 1; i < 8; ++i) w |= __float_as_uint(t[i]) << (2 * i);
+    return w & 0xffffu;
+}
+
+// One lane's 8 codes: a 32-bit word (4-bit codes) or a 16-bit word (2-bit codes).
+template <int BITS>
+__device__ __forceinline__ void store_codes8(char* p, const float (&t)[8]) {
+    if constexpr (BITS == 4) *reinterpret_cast<uint32_t*>(p) = pack8(t);
+    else *reinterpret_cast<uint16_t*>(p) = (uint16_t)pack8_2bit(t);
+}
+template <int BITS>
+__device__ __forceinline__ uint32_t load_codes8(const char* p) {
+    if constexpr (BITS == 4) return *reinterpret_cast<const uint32_t*>(p);
+    else return *reinterpret_cast<const uint16_t*>(p);
+}
+
+// 1 / s for a scale of BITS-bit codes.  With 15 steps s <= FLT_MAX / 15 < 2^126 and the
+// quotient is always normal; with 3 steps s can exceed 2^126, where the quotient is
+// sub-normal and the short sequence does not hold: those (astronomically wide) groups take
+// the full IEEE division.
+template <int BITS>
+__device__ __forceinline__ float rcp_scale(float s) {
+    if constexpr (BITS == 2) {
+        if (s > 0x1p126f) return __fdiv_rn(1.0f, s);
+    }
+    return rcp_exact(s);
+}
 
 template <typename T> struct elem_bytes;
 template <> struct elem_bytes<In_f32> { static constexpr int value = 4; };

@@ -27,9 +27,10 @@ namespace {
 
 constexpr int kUnroll = 2;  // token rows per lane and loop trip
 
-template <typename IN, int LPG, bool SEPARATE_SUMMARY>
+template <typename IN, int LPG, bool SEPARATE_SUMMARY, int BITS>
 __global__ void __launch_bounds__(kBlock) quantize_append_kernel(const QuantArgs a) {
     constexpr int EB = elem_bytes<IN>::value;
+    constexpr uint32_t CW = BITS;  // bytes of packed codes per lane and row (8 channels)
     const int H = a.n_kv_heads, d = a.head_dim, G = a.group_tokens;
 
     const int h = blockIdx.x;
@@ -53,11 +54,11 @@ __global__ void __launch_bounds__(kBlock) quantize_append_kernel(const QuantArgs
     const int64_t in_off = f * a.stride_frame + li * a.stride_layer + h * a.stride_head;
     const char* src = static_cast<const char*>(kv ? a.v : a.k) + in_off * EB;
     const int64_t tile = (((int64_t)l * 2 + kv) * a.capacity_groups + t) * H + h;
-    char* codes_t = reinterpret_cast<char*>(a.codes + tile * ((int64_t)G * d / 2));
+    char* codes_t = reinterpret_cast<char*>(a.codes + tile * ((int64_t)G * d * BITS / 8));
     f32x2* meta_t = reinterpret_cast<f32x2*>(a.meta) + tile * ((int64_t)G * ng);
     const uint32_t in_row_bytes = (uint32_t)a.stride_token * EB;
     const uint32_t in_lane = (uint32_t)row0 * in_row_bytes + (uint32_t)slot * 8u * EB;
-    const uint32_t code_lane = ((uint32_t)row0 * lpr + slot) * 4u;
+    const uint32_t code_lane = ((uint32_t)row0 * lpr + slot) * CW;
     const int meta_lane = row0 * ng + slot / LPG;
     const bool meta_writer = (slot & (LPG - 1)) == 0;
 
@@ -94,10 +95,10 @@ __global__ void __launch_bounds__(kBlock) quantize_append_kernel(const QuantArgs
             }
             group_minmax<LPG>(mn, mx);
             mn = mn + 0.0f;  // never store -0 as a zero point
-            float s = div15_exact(__fsub_rn(mx, mn));
+            float s = div_levels_exact<BITS>(__fsub_rn(mx, mn));
             float inv;
             if (s >= 1.17549435e-38f) {
-                inv = rcp_exact(s);
+                inv = rcp_scale<BITS>(s);
             } else {  // flat or sub-normal range: all codes 0
                 s = 0.0f;
                 inv = 0.0f;
@@ -106,9 +107,8 @@ __global__ void __launch_bounds__(kBlock) quantize_append_kernel(const QuantArgs
 #pragma unroll
             for (int i = 0; i < 8; ++i)
                 tq[i] = __builtin_fmaf(__fsub_rn(x[i], mn), inv, 8388608.0f);
-            const uint32_t packed = pack8(tq);
             if (ok) {
-                *reinterpret_cast<uint32_t*>(codes_t + (code_lane + (uint32_t)rb * lpr * 4u)) = packed;
+                store_codes8<BITS>(codes_t + (code_lane + (uint32_t)rb * lpr * CW), tq);
                 if (meta_writer) {
                     const f32x2 sm = {s, mn};
                     meta_t[meta_lane + rb * ng] = sm;
@@ -159,15 +159,20 @@ __global__ void __launch_bounds__(kBlock) quantize_append_kernel(const QuantArgs
     }
 }
 
+template <typename IN, int LPG, int BITS>
+hipError_t launch_b(const QuantArgs& a, hipStream_t s) {
+    const dim3 grid(a.n_kv_heads, 2 * a.n_layers, a.n_frames);
+    if (a.ksum != a.k)
+        quantize_append_kernel<IN, LPG, true, BITS><<<grid, dim3(kBlock), 0, s>>>(a);
+    else
+        quantize_append_kernel<IN, LPG, false, BITS><<<grid, dim3(kBlock), 0, s>>>(a);
+    return hipGetLastError();
+}
+
 template <typename IN, int LPG>
 hipError_t launch_t(const QuantArgs& a, hipStream_t s) {
     if (a.n_frames == 0 || a.n_layers == 0) return hipSuccess;
-    const dim3 grid(a.n_kv_heads, 2 * a.n_layers, a.n_frames);
-    if (a.ksum != a.k)
-        quantize_append_kernel<IN, LPG, true><<<grid, dim3(kBlock), 0, s>>>(a);
-    else
-        quantize_append_kernel<IN, LPG, false><<<grid, dim3(kBlock), 0, s>>>(a);
-    return hipGetLastError();
+    return a.bits == 2 ? launch_b<IN, LPG, 2>(a, s) : launch_b<IN, LPG, 4>(a, s);
 }
 
 template <typename IN>

@@ -18,9 +18,10 @@ namespace {
 
 constexpr int kUnroll = 2;
 
-template <typename IN, bool SEPARATE_SUMMARY, int HOLD>
+template <typename IN, bool SEPARATE_SUMMARY, int HOLD, int BITS>
 __global__ void __launch_bounds__(kBlock) quantize_append_tokens_kernel(const QuantArgs a) {
     constexpr int EB = elem_bytes<IN>::value;
+    constexpr uint32_t CW = BITS;  // bytes of packed codes per lane and row (8 channels)
     const int H = a.n_kv_heads, d = a.head_dim, G = a.group_tokens;
     const int h = blockIdx.x;
     const int kv = blockIdx.y & 1;
@@ -39,11 +40,11 @@ __global__ void __launch_bounds__(kBlock) quantize_append_tokens_kernel(const Qu
     const int64_t in_off = f * a.stride_frame + li * a.stride_layer + h * a.stride_head;
     const char* src = static_cast<const char*>(kv ? a.v : a.k) + in_off * EB;
     const int64_t tile = (((int64_t)l * 2 + kv) * a.capacity_groups + t) * H + h;
-    char* codes_t = reinterpret_cast<char*>(a.codes + tile * ((int64_t)G * d / 2));
+    char* codes_t = reinterpret_cast<char*>(a.codes + tile * ((int64_t)G * d * BITS / 8));
     f32x2* meta_t = reinterpret_cast<f32x2*>(a.meta) + tile * (int64_t)d;  // [d] (scale, zero)
     const uint32_t in_row_bytes = (uint32_t)a.stride_token * EB;
     const uint32_t in_lane = (uint32_t)row0 * in_row_bytes + (uint32_t)slot * 8u * EB;
-    const uint32_t code_lane = ((uint32_t)row0 * lpr + slot) * 4u;
+    const uint32_t code_lane = ((uint32_t)row0 * lpr + slot) * CW;
 
     __shared__ double shared_buf[kBlock * 8];        // 16 KB: (min, max) per row slot, then key sums
     extern __shared__ f32x2 fin[];                    // [d] (zero point, 1/scale) per channel
@@ -110,10 +111,10 @@ __global__ void __launch_bounds__(kBlock) quantize_append_tokens_kernel(const Qu
             cmx = fmaxf(cmx, mm[r * d + c][1]);
         }
         cmn = cmn + 0.0f;  // never store -0 as a zero point
-        float s = div15_exact(__fsub_rn(cmx, cmn));
+        float s = div_levels_exact<BITS>(__fsub_rn(cmx, cmn));
         float inv;
         if (s >= 1.17549435e-38f) {
-            inv = rcp_exact(s);
+            inv = rcp_scale<BITS>(s);
         } else {
             s = 0.0f;
             inv = 0.0f;
@@ -137,7 +138,7 @@ __global__ void __launch_bounds__(kBlock) quantize_append_tokens_kernel(const Qu
             widen(raw, x);
 #pragma unroll
             for (int i = 0; i < 8; ++i) tq[i] = __builtin_fmaf(__fsub_rn(x[i], zm[i]), zi[i], 8388608.0f);
-            *reinterpret_cast<uint32_t*>(codes_t + (code_lane + (uint32_t)rb * lpr * 4u)) = pack8(tq);
+            store_codes8<BITS>(codes_t + (code_lane + (uint32_t)rb * lpr * CW), tq);
         };
         if (HOLD > 0) {
 #pragma unroll
@@ -185,10 +186,17 @@ template <typename IN, int HOLD>
 hipError_t launch_h(const QuantArgs& a, hipStream_t s) {
     const dim3 grid(a.n_kv_heads, 2 * a.n_layers, a.n_frames);
     const size_t lds = (size_t)a.head_dim * sizeof(f32x2);
-    if (a.ksum != a.k)
-        quantize_append_tokens_kernel<IN, true, HOLD><<<grid, dim3(kBlock), lds, s>>>(a);
-    else
-        quantize_append_tokens_kernel<IN, false, HOLD><<<grid, dim3(kBlock), lds, s>>>(a);
+    if (a.bits == 2) {
+        if (a.ksum != a.k)
+            quantize_append_tokens_kernel<IN, true, HOLD, 2><<<grid, dim3(kBlock), lds, s>>>(a);
+        else
+            quantize_append_tokens_kernel<IN, false, HOLD, 2><<<grid, dim3(kBlock), lds, s>>>(a);
+    } else {
+        if (a.ksum != a.k)
+            quantize_append_tokens_kernel<IN, true, HOLD, 4><<<grid, dim3(kBlock), lds, s>>>(a);
+        else
+            quantize_append_tokens_kernel<IN, false, HOLD, 4><<<grid, dim3(kBlock), lds, s>>>(a);
+    }
     return hipGetLastError();
 }
 

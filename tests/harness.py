@@ -17,23 +17,23 @@ def bits(t: torch.Tensor) -> np.ndarray:
 
 
 def make_pair(oqm, *, n_layers, n_kv_heads, n_q_heads, head_dim, group_tokens, qgroup, capacity,
-              in_dtype="bf16", out_dtype=None, sim="cosine", qaxis=0):
+              in_dtype="bf16", out_dtype=None, sim="cosine", qaxis=0, bits=4):
     out_dtype = out_dtype or in_dtype
     simc = 1 if sim == "cosine" else 0
     ocfg = orc.make_config(n_layers, n_kv_heads, n_q_heads, head_dim, group_tokens, qgroup,
-                           capacity, qaxis=qaxis, in_dtype=DT[in_dtype][0], out_dtype=DT[out_dtype][0],
-                           sim=simc)
+                           capacity, qaxis=qaxis, bits=bits, in_dtype=DT[in_dtype][0],
+                           out_dtype=DT[out_dtype][0], sim=simc)
     gcfg = oqm.make_config(n_layers, n_kv_heads, n_q_heads, head_dim, group_tokens, qgroup,
-                           capacity, qaxis=qaxis, in_dtype=DT[in_dtype][0], out_dtype=DT[out_dtype][0],
-                           sim=simc)
+                           capacity, qaxis=qaxis, bits=bits, in_dtype=DT[in_dtype][0],
+                           out_dtype=DT[out_dtype][0], sim=simc)
     return orc.new_store(ocfg), oqm.Memory.allocate(gcfg)
 
 
-def pair_for(oqm, w: synth_kv.Workload, capacity=None, out_dtype=None, qaxis=0):
+def pair_for(oqm, w: synth_kv.Workload, capacity=None, out_dtype=None, qaxis=0, bits=4):
     return make_pair(oqm, n_layers=w.n_layers, n_kv_heads=w.n_kv_heads, n_q_heads=w.n_q_heads,
                      head_dim=w.head_dim, group_tokens=w.group_tokens, qgroup=w.qgroup,
                      capacity=capacity or w.n_frames, in_dtype=w.dtype, out_dtype=out_dtype,
-                     sim=w.sim, qaxis=qaxis)
+                     sim=w.sim, qaxis=qaxis, bits=bits)
 
 
 def append_both(oqm, st, mem, k: torch.Tensor, v: torch.Tensor, ksum: torch.Tensor | None = None):
@@ -51,7 +51,7 @@ def storage_views(cfg, codes, scale, zero, keys):
     L, T, H, G, d, gs = (cfg.n_layers, cfg.capacity_groups, cfg.n_kv_heads, cfg.group_tokens,
                          cfg.head_dim, cfg.qgroup)
     mshape = (L, 2, T, H, G, d // gs) if cfg.qaxis == 0 else (L, 2, T, H, d)
-    return (codes.reshape(L, 2, T, H, G, d // 2), scale.reshape(mshape), zero.reshape(mshape),
+    return (codes.reshape(L, 2, T, H, G, d * cfg.bits // 8), scale.reshape(mshape), zero.reshape(mshape),
             keys.reshape(L, T, H, d))
 
 

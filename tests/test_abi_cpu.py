@@ -46,7 +46,7 @@ def test_sizes_follow_the_documented_layout(oqm):
 
 @pytest.mark.parametrize("field,value,status", [
     ("head_dim", 100, "INVALID"), ("qgroup", 48, "INVALID"), ("qgroup", 4, "UNSUPPORTED"),
-    ("bits", 3, "INVALID"), ("bits", 2, "UNSUPPORTED"), ("n_q_heads", 27, "INVALID"),
+    ("bits", 3, "INVALID"), ("bits", 8, "INVALID"), ("n_q_heads", 27, "INVALID"),
     ("group_tokens", 0, "INVALID"), ("capacity_groups", 0, "INVALID"), ("in_dtype", 7, "INVALID"),
     ("sim", 2, "INVALID"), ("qaxis", 5, "INVALID")])
 def test_bad_configurations_are_rejected(oqm, field, value, status):
@@ -144,6 +144,13 @@ def test_assemble_and_retrieve_validation(oqm):
         assert e.value.status == oqm.TOM_ERR_INVALID_ARG and "k_out" in str(e.value)
     finally:
         oqm.tom_oqm_destroy(h)
+
+
+def test_two_bit_sizes(oqm):
+    cfg = oqm.make_config(28, 4, 28, 128, 50, 64, 100, bits=2)
+    s = oqm.tom_oqm_query_sizes(cfg)
+    tiles = 28 * 2 * 100 * 4
+    assert s.codes == tiles * 50 * 32 and s.meta == tiles * 50 * 2 * 2 * 4
 
 
 def test_token_axis_sizes(oqm):

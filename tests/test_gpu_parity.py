@@ -21,8 +21,8 @@ def oqm():
 
 
 def _stream_and_check(oqm, w, frames_per_call, k=None, path=None, want_tokens=False, out_dtype=None,
-                      qaxis=0):
-    st, mem = H.pair_for(oqm, w, out_dtype=out_dtype, qaxis=qaxis)
+                      qaxis=0, bits=4):
+    st, mem = H.pair_for(oqm, w, out_dtype=out_dtype, qaxis=qaxis, bits=bits)
     try:
         f = 0
         while f < w.n_frames:
@@ -84,6 +84,38 @@ def test_token_axis_quantizer(oqm, G, d, dt, H_k, H_q):
     w = synth_kv.Workload("X", 2, H_k, H_q, d, G, 9, 64, 5, 4, dt, "cosine", 300 + G + d, "outlier", 9)
     r = _stream_and_check(oqm, w, 4, qaxis=1)
     assert r["k_eff"] == 4 and r["loose_rows"] == 0
+
+
+@pytest.mark.parametrize("qaxis,G,d,gs,dt,H_k,H_q", [
+    (0, 196, 128, 64, "bf16", 4, 28), (0, 50, 128, 32, "f16", 4, 28), (1, 50, 128, 64, "f16", 4, 28),
+    (1, 196, 128, 64, "bf16", 4, 28), (0, 13, 96, 8, "f32", 3, 6), (1, 300, 64, 64, "bf16", 2, 2),
+    (0, 1, 8, 8, "f32", 1, 1), (0, 33, 256, 128, "bf16", 2, 4)])
+def test_two_bit_codes(oqm, qaxis, G, d, gs, dt, H_k, H_q):
+    """The paper's bit-width ablation: 2-bit codes (three steps between min and max), four per
+    byte, on both quantization axes."""
+    w = synth_kv.Workload("X", 2, H_k, H_q, d, G, 10, gs, 5, 4, dt, "cosine", 700 + G + d, "outlier", 10)
+    r = _stream_and_check(oqm, w, 4, qaxis=qaxis, bits=2)
+    assert r["k_eff"] == 4 and r["loose_rows"] == 0
+
+
+def test_two_bit_extreme_ranges(oqm):
+    """Steps above 2^126 (their reciprocal is sub-normal), flat and sub-normal-step groups."""
+    for qaxis in (0, 1):
+        st, mem = H.make_pair(oqm, n_layers=1, n_kv_heads=2, n_q_heads=2, head_dim=64, group_tokens=9,
+                              qgroup=32, capacity=3, in_dtype="f32", qaxis=qaxis, bits=2)
+        try:
+            g = torch.Generator().manual_seed(12)
+            k = torch.randn(3, 1, 2, 9, 64, generator=g)
+            k[0] *= 1.2e38                                           # range up to ~3e38: s > 2^126
+            k[0].clamp_(-1.6e38, 1.6e38)
+            k[1, 0, 0] = 2.5
+            k[1, 0, 1, :, :32] = torch.linspace(0, 2e-38, 32)       # sub-normal step
+            k[2, 0, 0, 0, 0] = 1.7e38                                # max - min = 3.4e38, just finite
+            k[2, 0, 0, 1, 0] = -1.7e38
+            H.append_both(oqm, st, mem, k, -k)
+            H.compare_storage(st, mem)
+        finally:
+            mem.close()
 
 
 def test_mixed_in_out_dtypes(oqm):
@@ -336,3 +368,4 @@ def test_division_shortcuts_are_exact_for_every_input():
     r = subprocess.run([exe], capture_output=True, text=True, timeout=100)
     assert r.returncode == 0, r.stdout + r.stderr
     assert "div15_exact mismatches: 0" in r.stdout and "rcp_exact mismatches: 0" in r.stdout
+    assert "div3_exact mismatches: 0" in r.stdout
