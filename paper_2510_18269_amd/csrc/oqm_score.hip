@@ -38,40 +38,56 @@ __global__ void __launch_bounds__(kBlock) query_fold_kernel(const ScoreArgs a, c
     double acc[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[i] = 0.0;
+    const double inv_r = 1.0 / (double)r;
     if (active) {
-        for (int j = jl; j < Tq; j += jn) {
-            double qt[8];
+        // Two tokens per trip; for GQA blocks of up to 8 heads all their loads are issued
+        // before the first is used (one memory round trip for T_q <= 2 * jn).
+        constexpr int kTok = 2, kHeads = 8;
+        for (int j0 = jl; j0 < Tq; j0 += kTok * jn) {
+            double qt[kTok][8];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) qt[i] = 0.0;
-            // the r heads of the GQA block, eight loads in flight at a time
-            for (int g0 = 0; g0 < r; g0 += 8) {
-                Raw8<QT> raw[8];
+            for (int u = 0; u < kTok; ++u)
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    zero_raw(raw[u]);
-                    if (g0 + u < r) {
-                        const int64_t off =
-                            (((int64_t)li * Hq + (h * r + g0 + u)) * Tq + j) * d + slot * 8;
-                        load_raw(q + off * EB, raw[u]);
+                for (int i = 0; i < 8; ++i) qt[u][i] = 0.0;
+            for (int g0 = 0; g0 < r; g0 += kHeads) {
+                Raw8<QT> raw[kTok][kHeads];
+#pragma unroll
+                for (int u = 0; u < kTok; ++u) {
+                    const int j = j0 + u * jn;
+#pragma unroll
+                    for (int g = 0; g < kHeads; ++g) {
+                        zero_raw(raw[u][g]);
+                        if (j < Tq && g0 + g < r) {
+                            const int64_t off =
+                                (((int64_t)li * Hq + (h * r + g0 + g)) * Tq + j) * d + slot * 8;
+                            load_raw(q + off * EB, raw[u][g]);
+                        }
                     }
                 }
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    float x[8];
-                    widen(raw[u], x);  // heads past the block were zero-filled
+                for (int u = 0; u < kTok; ++u)
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) qt[i] += (double)x[i];
+                    for (int g = 0; g < kHeads; ++g) {
+                        float x[8];
+                        widen(raw[u][g], x);  // heads past the block and tokens past T_q were zero-filled
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) qt[u][i] += (double)x[i];
+                    }
+            }
+#pragma unroll
+            for (int u = 0; u < kTok; ++u) {
+                const int j = j0 + u * jn;
+                if (j >= Tq) break;
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    qt[u][i] = qt[u][i] * inv_r;
+                    acc[i] += qt[u][i];
                 }
-            }
+                if (want_tokens) {
+                    double* dst = a.ws_qtok + ((int64_t)li * Tq + j) * HD + (int64_t)h * d + slot * 8;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                qt[i] = qt[i] / (double)r;
-                acc[i] += qt[i];
-            }
-            if (want_tokens) {
-                double* dst = a.ws_qtok + ((int64_t)li * Tq + j) * HD + (int64_t)h * d + slot * 8;
-#pragma unroll
-                for (int i = 0; i < 8; ++i) dst[i] = qt[i];
+                    for (int i = 0; i < 8; ++i) dst[i] = qt[u][i];
+                }
             }
         }
     }
@@ -86,7 +102,7 @@ __global__ void __launch_bounds__(kBlock) query_fold_kernel(const ScoreArgs a, c
     for (int c = tid; c < d; c += kBlock) {
         double sum = 0.0;
         for (int j = 0; j < jn; ++j) sum += red[j * d + c];
-        const double qb = sum / (double)Tq;
+        const double qb = sum * (1.0 / (double)Tq);
         a.ws_qbar[(int64_t)li * HD + (int64_t)h * d + c] = qb;
         sq += qb * qb;
     }
@@ -101,66 +117,78 @@ __global__ void __launch_bounds__(kBlock) query_fold_kernel(const ScoreArgs a, c
 }
 
 // ------------------------------------------------------------------ mean-query GEMV
-constexpr int kGroupsPerWave = 4;  // scored together: their key loads are all in flight at once
+// Sum of a double over an aligned set of 16 lanes (DPP swaps; valid in all 16 lanes).
+template <int CTRL>
+__device__ __forceinline__ double dpp_f64(double v) {
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, 0xF, 0xF, true);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, 0xF, 0xF, true);
+    return __hiloint2double(hi, lo);
+}
+__device__ __forceinline__ double row16_sum_f64(double v) {
+    v += dpp_f64<0xB1>(v);   // lane ^ 1
+    v += dpp_f64<0x4E>(v);   // lane ^ 2
+    v += dpp_f64<0x141>(v);  // the other quad of the 8
+    v += dpp_f64<0x140>(v);  // the other half of the 16
+    return v;
+}
 
-// grid (ceil(T / (4 * kGroupsPerWave)), n_layers); dynamic LDS: H_k*d doubles (q-bar).
+constexpr int kScoreChunks = 8;  // 16-byte key loads per lane that are in flight together
+
+// grid (ceil(T / 16), n_layers); dynamic LDS: H_k*d doubles (q-bar).  16 lanes share one
+// frame-group: lane i of them takes floats [64c + 4i, 64c + 4i + 4) of the key for
+// c = 0, 1, ..., so every load instruction of the 16 lanes covers 256 contiguous bytes and a
+// 512-float key is fetched by one batch of 8 loads per lane.
 __global__ void __launch_bounds__(kBlock) score_mean_query_kernel(const ScoreArgs a) {
     extern __shared__ double qbar[];
     const int li = blockIdx.y;
     const int HD = a.n_kv_heads * a.head_dim;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, sub = tid & 15;
     const float* keys = a.keys + ((int64_t)(a.layer0 + li) * a.capacity_groups) * HD;
-    const int t0 = (blockIdx.x * (kBlock / 64) + wave) * kGroupsPerWave;
-    const bool live = t0 < a.n_groups;  // uniform per wave
+    const int t = blockIdx.x * (kBlock / 16) + (tid >> 4);
+    const int tc = min(t, a.n_groups - 1);  // the tail re-reads the last group
+    const float* key = keys + (int64_t)tc * HD + sub * 4;
     // The first key loads do not depend on the query: issue them before q-bar is staged.
-    f32x4 kx[kGroupsPerWave];
-    auto load_keys = [&](int e) {
+    f32x4 kx[kScoreChunks];
+    auto load_keys = [&](int e0) {
 #pragma unroll
-        for (int g = 0; g < kGroupsPerWave; ++g) {
-            const int t = min(t0 + g, a.n_groups - 1);  // the tail re-reads the last group
-            kx[g] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-            if (live && e < HD) kx[g] = *reinterpret_cast<const f32x4*>(keys + (int64_t)t * HD + e);
+        for (int c = 0; c < kScoreChunks; ++c) {
+            kx[c] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+            if (e0 + c * 64 + sub * 4 < HD) kx[c] = *reinterpret_cast<const f32x4*>(key + e0 + c * 64);
         }
     };
-    load_keys(lane * 4);
+    load_keys(0);
 
     for (int e = tid; e < HD; e += kBlock) qbar[e] = a.ws_qbar[(int64_t)li * HD + e];
     double nq2 = 0.0;
     for (int hh = 0; hh < a.n_kv_heads; ++hh) nq2 += a.ws_qnorm2[(int64_t)li * a.n_kv_heads + hh];
     const double nq = sqrt(nq2);
     __syncthreads();
-    if (!live) return;  // no barrier follows
 
-    double dot[kGroupsPerWave], nk2[kGroupsPerWave];
+    double dot = 0.0, nk2 = 0.0;
+    for (int e0 = 0; e0 < HD; e0 += kScoreChunks * 64) {
+        f32x4 cur[kScoreChunks];
 #pragma unroll
-    for (int g = 0; g < kGroupsPerWave; ++g) dot[g] = nk2[g] = 0.0;
-    for (int e = lane * 4; e < HD; e += 256) {
-        f32x4 cur[kGroupsPerWave];
+        for (int c = 0; c < kScoreChunks; ++c) cur[c] = kx[c];
+        if (e0 + kScoreChunks * 64 < HD) load_keys(e0 + kScoreChunks * 64);  // uniform
 #pragma unroll
-        for (int g = 0; g < kGroupsPerWave; ++g) cur[g] = kx[g];
-        load_keys(e + 256);  // next chunk in flight while this one is accumulated
-        double qv[4];
+        for (int c = 0; c < kScoreChunks; ++c) {
+            const int e = e0 + c * 64 + sub * 4;
+            if (e < HD) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) qv[i] = qbar[e + i];
-#pragma unroll
-        for (int g = 0; g < kGroupsPerWave; ++g) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const double kd = (double)cur[g][i];
-                dot[g] = fma(qv[i], kd, dot[g]);
-                nk2[g] = fma(kd, kd, nk2[g]);
+                for (int i = 0; i < 4; ++i) {
+                    const double kd = (double)cur[c][i];
+                    dot = fma(qbar[e + i], kd, dot);
+                    nk2 = fma(kd, kd, nk2);
+                }
             }
         }
     }
-#pragma unroll
-    for (int g = 0; g < kGroupsPerWave; ++g) {
-        const double dsum = wave_sum_f64(dot[g]);
-        const double nsum = wave_sum_f64(nk2[g]);
-        if (lane == 0 && t0 + g < a.n_groups) {
-            double s = dsum;
-            if (a.sim == TOM_SIM_COSINE) s = dsum / (fmax(nq, 1e-12) * fmax(sqrt(nsum), 1e-12));
-            a.scores[(int64_t)li * a.score_stride + t0 + g] = (float)s;
-        }
+    dot = row16_sum_f64(dot);
+    nk2 = row16_sum_f64(nk2);
+    if (sub == 0 && t < a.n_groups) {
+        double s = dot;
+        if (a.sim == TOM_SIM_COSINE) s = dot / (fmax(nq, 1e-12) * fmax(sqrt(nk2), 1e-12));
+        a.scores[(int64_t)li * a.score_stride + t] = (float)s;
     }
 }
 
@@ -335,7 +363,7 @@ hipError_t launch_query_fold(const ScoreArgs& a, bool want_tokens, hipStream_t s
 
 hipError_t launch_score_mean_query(const ScoreArgs& a, hipStream_t s) {
     if (a.n_layers == 0 || a.n_groups == 0) return hipSuccess;
-    const int per_block = (kBlock / 64) * kGroupsPerWave;
+    const int per_block = kBlock / 16;
     const dim3 grid((a.n_groups + per_block - 1) / per_block, a.n_layers);
     const size_t lds = (size_t)a.n_kv_heads * a.head_dim * sizeof(double);
     score_mean_query_kernel<<<grid, dim3(kBlock), lds, s>>>(a);
