@@ -291,6 +291,14 @@ def main():
                             "algorithmic_bytes": b_app, "avg_launch_us": round(ms_append * 1e3, 2)},
     }
 
+    if path == oqm.TOM_SCORE_TOKEN_GEMM:
+        # the per-token contraction runs on the float64 matrix cores: 2 * T_q * H_k*d flop per group
+        flop = 2.0 * w.t_q * w.n_kv_heads * w.head_dim * T * L
+        out["roofline_score"] = {"bound": "mfma", "kernel": "score_token_gemm_kernel (+ query fold)",
+                                 "achieved": round(flop / (ms_score * 1e-3) / 1e12, 2), "peak": 78.6,
+                                 "unit": "TFLOP/s", "frac": round(flop / (ms_score * 1e-3) / 1e12 / 78.6, 4),
+                                 "traffic": measured_traffic("score_token_gemm_kernel", w.name) if default_variant else None,
+                                 "flop": flop, "avg_launch_us": round(ms_score * 1e3, 2)}
     if not args.no_cpu_baseline:
         nb = max(1, args.cpu_sample_batches if fpa > 1 else 64)
         host = [(k.cpu(), v.cpu()) for k, v in batches[:min(nb, n_batches)]]
