@@ -356,6 +356,79 @@ def test_assemble_with_system_prefix_and_one_call_retrieve(oqm, qaxis, G, prefix
         mem.close()
 
 
+def test_layer_by_layer_calls_match_the_all_layer_call(oqm):
+    """Inside a model's forward pass the retrieval runs one layer at a time (layer0 = l,
+    n_layers = 1): every step must give what the all-layer call gives, i.e. the oracle's."""
+    w = synth_kv.Workload("X", 4, 4, 28, 128, 50, 30, 64, 8, 5, "bf16", "cosine", 811, "layer_std", 30)
+    st, mem = H.pair_for(oqm, w)
+    try:
+        kk, vv = synth_kv.kv_frames(w, 0, w.n_frames)
+        H.append_both(oqm, st, mem, kk, vv)
+        q = synth_kv.query(w)
+        L, Hk, G, d, k = w.n_layers, w.n_kv_heads, w.group_tokens, w.head_dim, w.top_k
+        ref_scores = H.orc.score_groups(st, H.bits(q), 1)
+        ref_idx, k_eff = H.orc.topk(ref_scores, k)
+        ref_k, ref_v = H.orc.dequant_gather(st, ref_idx, k_eff)
+        qd = q.cuda()
+        for path in (oqm.TOM_SCORE_MEAN_QUERY, oqm.TOM_SCORE_TOKEN_GEMM):
+            for l in (2, 0, 3, 1):                                 # any order
+                ws = torch.empty(oqm.tom_oqm_score_workspace_bytes(mem.handle, 1, w.t_q, path), dtype=torch.uint8,
+                                 device="cuda")
+                sc = torch.empty((1, w.n_frames), dtype=torch.float32, device="cuda")
+                idx = torch.full((1, k), -7, dtype=torch.int32, device="cuda")
+                ko = torch.zeros((1, Hk, k * G, d), dtype=torch.bfloat16, device="cuda")
+                vo = torch.zeros_like(ko)
+                oqm.tom_oqm_score_groups(mem.handle, l, 1, qd[l:l + 1].contiguous(), w.t_q, sc, w.n_frames, None,
+                                         path, ws)
+                assert oqm.tom_oqm_topk(sc, w.n_frames, 1, w.n_frames, k, idx) == k_eff
+                oqm.tom_oqm_dequant_gather(mem.handle, l, 1, idx, k, k_eff, ko, vo)
+                torch.cuda.synchronize()
+                got = sc.cpu().numpy().astype(np.float64)
+                assert np.all(np.abs(got - ref_scores[l:l + 1]) <= H.score_bound(st, q, ref_scores[l:l + 1]))
+                assert np.array_equal(idx.cpu().numpy(), ref_idx[l:l + 1])
+                assert np.array_equal(H.bits(ko), ref_k[l:l + 1]) and np.array_equal(H.bits(vo), ref_v[l:l + 1])
+                # the one-call form on the same single layer
+                ko.zero_()
+                vo.zero_()
+                idx.fill_(-7)
+                assert oqm.tom_oqm_retrieve(mem.handle, l, 1, qd[l:l + 1].contiguous(), w.t_q, k, sc, w.n_frames,
+                                            idx, ko, vo, ws, path=path) == k_eff
+                torch.cuda.synchronize()
+                assert np.array_equal(idx.cpu().numpy(), ref_idx[l:l + 1])
+                assert np.array_equal(H.bits(ko), ref_k[l:l + 1]) and np.array_equal(H.bits(vo), ref_v[l:l + 1])
+    finally:
+        mem.close()
+
+
+def test_random_configurations_sweep(oqm):
+    """Seeded random shapes, dtypes, axes, code widths and call patterns, each streamed through
+    the whole path and compared with the oracle element by element."""
+    rng = np.random.default_rng(20251018)
+    for case in range(24):
+        d = int(rng.choice([8, 16, 32, 64, 96, 128, 160, 256]))
+        gs_all = [g for g in (8, 16, 32, 64, 128) if d % g == 0]
+        gs = int(rng.choice(gs_all))
+        Hk = int(rng.integers(1, 5))
+        r = int(rng.choice([1, 2, 7]))
+        G = int(rng.choice([1, 3, 16, 31, 50, 64, 100, 196, 211]))
+        L = int(rng.integers(1, 4))
+        T = int(rng.integers(3, 20))
+        dt = str(rng.choice(["f32", "bf16", "f16"]))
+        qaxis = int(rng.integers(0, 2))
+        bits = int(rng.choice([4, 2]))
+        tq = int(rng.choice([1, 5, 16, 33]))
+        k = int(rng.integers(1, T + 3))
+        per_call = int(rng.integers(1, T + 1))
+        sim = str(rng.choice(["cosine", "dot"]))
+        kind = str(rng.choice(["normal", "layer_std", "outlier"]))
+        path = oqm.TOM_SCORE_TOKEN_GEMM if rng.integers(0, 2) else None
+        w = synth_kv.Workload("R", L, Hk, Hk * r, d, G, T, gs, tq, k, dt, sim, 9000 + case, kind, per_call)
+        print(f"case {case}: {w} qaxis={qaxis} bits={bits} path={path}", flush=True)
+        res = _stream_and_check(oqm, w, per_call, path=path, want_tokens=path is not None, qaxis=qaxis,
+                                bits=bits)
+        assert res["k_eff"] == min(k, T)
+
+
 def test_division_shortcuts_are_exact_for_every_input():
     """The quantize kernel computes (max - min) / 15 and 1 / s with one FMA correction step
     instead of the full IEEE division sequence; the library's self-check program compares
