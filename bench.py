@@ -132,7 +132,8 @@ def main():
     ap.add_argument("--group-tokens", type=int, default=0, help="override G (the paper keeps 50)")
     ap.add_argument("--bits", type=int, default=4, choices=[4, 2], help="code width (2 = the paper's ablation)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-batches", type=int, default=12)
+    ap.add_argument("--cpu-sample-batches", type=int, default=32,
+                    help="append calls the oracle is timed on (32 x 32 frames = the whole C3 stream)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the path has no collectives); "
@@ -226,6 +227,28 @@ def main():
     copy_gbps = 5 * 2 * copy_src.numel() * 4 / (cev[0].elapsed_time(cev[1]) * 1e-3) / 1e9
     del copy_src, copy_dst
 
+    # what the machine reaches for the byte mix of the two big kernels: the library's
+    # arithmetic-free stream probes over rotating regions far larger than the last-level cache
+    def probe(mode, read_b, write_b):
+        items = 44 << 20
+        n_src, n_dst = (12, 4) if read_b < write_b else (4, 12)
+        src = torch.empty(items * read_b * n_src, dtype=torch.uint8, device=dev).random_()
+        dst = torch.empty(items * write_b * n_dst, dtype=torch.uint8, device=dev)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        reps = 12
+        for i in range(3 + reps):
+            if i == 3:
+                ev[0].record()
+            oqm.tom_oqm_stream_probe(mode, src.data_ptr() + (i % n_src) * items * read_b,
+                                     dst.data_ptr() + (i % n_dst) * items * write_b, items)
+        ev[1].record()
+        torch.cuda.synchronize()
+        return reps * items * (read_b + write_b) / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e9
+
+    probe_gather = probe(0, 4, 16)
+    probe_append = probe(1, 16, 4)
+    torch.cuda.empty_cache()
+
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -270,6 +293,9 @@ def main():
         },
         "pct_of_hbm_peak": round(100 * gbps(total_bytes, ms_step) / HBM_PEAK_GBPS, 2),
         "copy_GBps": round(copy_gbps, 1),
+        "probe": {"gather_mix_GBps": round(probe_gather, 1), "append_mix_GBps": round(probe_append, 1),
+                  "what": "arithmetic-free linear streams of the library with the kernels' read/write "
+                          "mix (4 B in / 16 B out, 16 B in / 4 B out), same run"},
         "bytes_per_step": total_bytes,
         "append": {"ms": round(ms_append, 4), "GBps": round(gbps(b_app, ms_append), 1),
                    "pct_of_peak": round(100 * gbps(b_app, ms_append) / HBM_PEAK_GBPS, 2),
@@ -282,11 +308,13 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "dequant_gather_kernel",
                      "achieved": round(gbps(b_gat, ms_gather), 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(gbps(b_gat, ms_gather) / HBM_PEAK_GBPS, 4),
+                     "frac_of_probe": round(gbps(b_gat, ms_gather) / probe_gather, 4),
                      "traffic": measured_traffic("dequant_gather_kernel", w.name) if default_variant else None,
                      "algorithmic_bytes": b_gat, "avg_launch_us": round(ms_gather * 1e3, 2)},
         "roofline_append": {"bound": "hbm", "kernel": "quantize_append_kernel",
                             "achieved": round(gbps(b_app, ms_append), 1), "peak": HBM_PEAK_GBPS,
                             "unit": "GB/s", "frac": round(gbps(b_app, ms_append) / HBM_PEAK_GBPS, 4),
+                            "frac_of_probe": round(gbps(b_app, ms_append) / probe_append, 4),
                             "traffic": measured_traffic("quantize_append_kernel", w.name) if default_variant else None,
                             "algorithmic_bytes": b_app, "avg_launch_us": round(ms_append * 1e3, 2)},
     }

@@ -283,6 +283,21 @@ tom_status_t tom_oqm_retrieve(const tom_oqm_t* h, int32_t layer0, int32_t n_laye
                               void* workspace_device, size_t workspace_bytes, int32_t* k_eff_host,
                               void* hip_stream);
 
+/*
+ * Measurement aid, not a step of the method (the supplement's implementation paragraphs
+ * give timings only; this is what lets a benchmark put a measured machine ceiling beside
+ * them): streams `items` units from src to dst with no arithmetic, one unit per thread,
+ * linear and coalesced, in the byte mix of one of the bandwidth-bound steps.
+ *   mode 0  reads  4 B, writes 16 B per item   (dequant-gather's mix)
+ *   mode 1  reads 16 B, writes  4 B per item   (quantize-append's mix)
+ *   mode 2  reads 16 B, writes 16 B per item   (copy)
+ *   src, dst  device, 16-byte aligned, items * (bytes read / written per item) large;
+ *             dst receives values derived from src (not a copy in modes 0 and 1).
+ * Errors: mode outside 0..2, items < 0, NULL or misaligned pointers -> INVALID_ARG.
+ */
+tom_status_t tom_oqm_stream_probe(int32_t mode, const void* src_device, void* dst_device,
+                                  int64_t items, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

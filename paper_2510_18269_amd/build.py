@@ -13,7 +13,8 @@ LIB = os.path.join(HERE, "libtom_oqm.so")
 OBJ = os.path.join(HERE, "_build")
 SELFCHECK = os.path.join(HERE, "selfcheck_division.bin")
 
-SOURCES = ["oqm_api.hip", "oqm_quantize.hip", "oqm_quantize_tokens.hip", "oqm_dequant.hip", "oqm_score.hip", "oqm_topk.hip"]
+SOURCES = ["oqm_api.hip", "oqm_quantize.hip", "oqm_quantize_tokens.hip", "oqm_dequant.hip", "oqm_score.hip", "oqm_topk.hip",
+           "oqm_probe.hip"]
 
 # -ffp-contract=off: the codes, scale/zero and dequantized values must be single, separately
 # rounded IEEE operations.  -fno-honor-nans (inputs are finite by contract) only lets min/max

@@ -392,4 +392,16 @@ tom_status_t tom_oqm_retrieve(const tom_oqm_t* h, int32_t layer0, int32_t n_laye
     return TOM_OK;
 }
 
+tom_status_t tom_oqm_stream_probe(int32_t mode, const void* src, void* dst, int64_t items,
+                                  void* hip_stream) {
+    if (mode < 0 || mode > 2) return fail(TOM_ERR_INVALID_ARG, "mode must be 0, 1 or 2");
+    if (items < 0) return fail(TOM_ERR_INVALID_ARG, "items < 0");
+    if (items == 0) return TOM_OK;
+    if (!src || !dst || !aligned16(src) || !aligned16(dst))
+        return fail(TOM_ERR_INVALID_ARG, "src and dst must be non-NULL and 16-byte aligned");
+    const hipError_t e = launch_stream_probe(mode, src, dst, items, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return fail(TOM_ERR_HIP, "stream probe launch: %s", hipGetErrorString(e));
+    return TOM_OK;
+}
+
 }  // extern "C"
