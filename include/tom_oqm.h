@@ -143,8 +143,9 @@ int32_t tom_oqm_k_from_budget(int64_t budget_tokens, int32_t group_tokens, int32
  * Quantizes n_frames frame-groups of layers [layer0, layer0 + n_layers) and
  * writes them to group slots T .. T + n_frames - 1, T = tom_oqm_num_groups(h).
  * Per quant-group (gs consecutive channels of one token, or with qaxis TOKENS
- * all G tokens of one channel): m = min, s = (max - min) / 15 in float32;
- * code = clamp(round_half_even(d * inv), 0, 15) with d = float32(x - m),
+ * all G tokens of one channel): m = min, s = (max - min) / n in float32 with
+ * n = 2^bits - 1 steps (15; 3 for 2-bit codes);
+ * code = clamp(round_half_even(d * inv), 0, n) with d = float32(x - m),
  * inv = float32(1 / s) computed once per quant-group, and the product d * inv
  * not rounded before the rounding to an integer; s below FLT_MIN (e.g.
  * max == min) is stored as 0 with all codes 0; m is stored as +0 rather than
