@@ -278,6 +278,14 @@ def main():
     torch.cuda.synchronize()
     ms_retrieve_call = rev[0].elapsed_time(rev[1]) / 20
 
+    # what an empty interval between two events reads: an upper bound of the events' own cost,
+    # which every per-kernel figure below includes (it matters for the short kernels)
+    oev = [torch.cuda.Event(enable_timing=True) for _ in range(21)]
+    for e in oev:
+        e.record()
+    torch.cuda.synchronize()
+    event_overhead_us = sum(oev[i].elapsed_time(oev[i + 1]) for i in range(20)) / 20 * 1e3
+
     def avg_ms(a, b):
         return sum(e[a].elapsed_time(e[b]) for e in events) / len(events)
 
@@ -323,6 +331,7 @@ def main():
         "topk": {"ms": round(ms_topk, 4)},
         "gather": {"ms": round(ms_gather, 4), "GBps": round(gbps(b_gat, ms_gather), 1),
                    "pct_of_peak": round(100 * gbps(b_gat, ms_gather) / HBM_PEAK_GBPS, 2), "bytes": b_gat},
+        "event_overhead_us": round(event_overhead_us, 2),
         "retrieval_ms_per_query": round(ms_retrieve_call, 4),
         "retrieval_ms_per_query_separate_calls": round(ms_score + ms_topk + ms_gather, 4),
         "roofline": {"bound": "hbm", "kernel": "dequant_gather_kernel",
