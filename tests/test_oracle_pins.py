@@ -513,6 +513,32 @@ def test_gather_rows_are_the_named_groups(oracle, out_dtype):
         assert err.max() <= 0.5 * scale.max() * (1 + 1e-4) + 1e-6
 
 
+@pytest.mark.parametrize("qaxis", [0, 1])
+def test_two_bit_store_and_gather(oracle, qaxis):
+    """The 2-bit variant through append and gather: four codes per byte, three steps between
+    min and max, reconstruction within half a step, Table 4's ratio for the code payload."""
+    cfg = _small_cfg(oracle, bits=2, qaxis=qaxis)
+    st = oracle.new_store(cfg)
+    r = _rng(77)
+    k = r.standard_normal((4, 2, 2, 5, 32)).astype(np.float32)
+    oracle.quantize_append(st, k, 2 * k)
+    assert st.codes.size == 2 * 2 * 9 * 2 * 5 * 32 // 4          # L * (K,V) * T_cap * H * G * d / 4
+    idx = np.array([[3, 0], [1, 2]], np.int32)
+    ko, vo = oracle.dequant_gather(st, idx, 2)
+    for l in range(2):
+        for rnk in range(2):
+            for h in range(2):
+                x = k[idx[l, rnk], l, h]
+                codes, packed, scale, zero = oracle.quantize_tile(x, 16, qaxis, 2)
+                assert codes.max() <= 3 and np.array_equal(oracle.tile_view(st, l, 0, idx[l, rnk], h)[0].ravel(),
+                                                           packed.ravel())
+                step = np.repeat(scale, 16, axis=1) if qaxis == 0 else np.broadcast_to(scale, x.shape)
+                got = ko[l, h, rnk * 5:(rnk + 1) * 5]
+                assert np.all(np.abs(got - x) <= 0.5 * step * (1 + 1e-5) + 1e-6)
+                assert np.allclose(vo[l, h, rnk * 5:(rnk + 1) * 5], 2 * got, rtol=1e-6, atol=1e-6)
+    assert oracle.lib().tomref_compression_ratio(196, 50, 2) == pytest.approx(196 * 16 / (50 * 2))
+
+
 def test_gather_rejects_bad_index(oracle):
     cfg = _small_cfg(oracle)
     st = oracle.new_store(cfg)
