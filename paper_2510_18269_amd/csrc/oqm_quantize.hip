@@ -148,14 +148,16 @@ __global__ void __launch_bounds__(kBlock) quantize_append_kernel(const QuantArgs
     // Summary key: column sums over the rpp row slots of the workgroup, in float64.
     if (active) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) shared_buf[row0 * d + slot * 8 + i] = acc[i];
+        for (int i = 0; i < 8; ++i) shared_buf[row0 * d + i * lpr + slot] = acc[i];
     }
     __syncthreads();
     float* key = a.keys + (((int64_t)l * a.capacity_groups + t) * H + h) * d;
-    for (int c = tid; c < d; c += kBlock) {
+    // position q = i * lpr + slot holds channel slot * 8 + i: the lanes of a wave write
+    // consecutive doubles (channel order would put them 64 bytes apart: 16-way bank conflicts)
+    for (int q = tid; q < d; q += kBlock) {
         double sum = 0.0;
-        for (int r = 0; r < rpp; ++r) sum += shared_buf[r * d + c];
-        key[c] = (float)(sum / (double)G);
+        for (int r = 0; r < rpp; ++r) sum += shared_buf[r * d + q];
+        key[(q % lpr) * 8 + q / lpr] = (float)(sum / (double)G);
     }
 }
 

@@ -100,15 +100,17 @@ __global__ void __launch_bounds__(kBlock) quantize_append_tokens_kernel(const Qu
     }
     if (active) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) mm[row0 * d + slot * 8 + i] = f32x2{mn[i], mx[i]};
+        for (int i = 0; i < 8; ++i) mm[row0 * d + i * lpr + slot] = f32x2{mn[i], mx[i]};  // position, not channel
     }
     __syncthreads();
-    // ---- one thread per channel: Eq. 9 over the whole token axis
-    for (int c = tid; c < d; c += kBlock) {
-        float cmn = mm[c][0], cmx = mm[c][1];
+    // ---- one thread per channel: Eq. 9 over the whole token axis.  The LDS arrays are indexed
+    // by position q = i * lpr + slot (channel slot * 8 + i), so that the lanes of a wave touch
+    // consecutive words instead of words 64 bytes apart (16-way bank conflicts otherwise).
+    for (int q = tid; q < d; q += kBlock) {
+        float cmn = mm[q][0], cmx = mm[q][1];
         for (int r = 1; r < rpp; ++r) {
-            cmn = fminf(cmn, mm[r * d + c][0]);
-            cmx = fmaxf(cmx, mm[r * d + c][1]);
+            cmn = fminf(cmn, mm[r * d + q][0]);
+            cmx = fmaxf(cmx, mm[r * d + q][1]);
         }
         cmn = cmn + 0.0f;  // never store -0 as a zero point
         float s = div_levels_exact<BITS>(__fsub_rn(cmx, cmn));
@@ -119,8 +121,9 @@ __global__ void __launch_bounds__(kBlock) quantize_append_tokens_kernel(const Qu
             s = 0.0f;
             inv = 0.0f;
         }
+        const int c = (q % lpr) * 8 + q / lpr;
         meta_t[c] = f32x2{s, cmn};
-        fin[c] = f32x2{cmn, inv};
+        fin[q] = f32x2{cmn, inv};
     }
     __syncthreads();
 
@@ -129,7 +132,7 @@ __global__ void __launch_bounds__(kBlock) quantize_append_tokens_kernel(const Qu
         float zm[8], zi[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            const f32x2 v = fin[slot * 8 + i];
+            const f32x2 v = fin[i * lpr + slot];
             zm[i] = v[0];
             zi[i] = v[1];
         }
@@ -171,14 +174,14 @@ __global__ void __launch_bounds__(kBlock) quantize_append_tokens_kernel(const Qu
     __syncthreads();  // the (min, max) use of shared_buf is over
     if (active) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) shared_buf[row0 * d + slot * 8 + i] = acc[i];
+        for (int i = 0; i < 8; ++i) shared_buf[row0 * d + i * lpr + slot] = acc[i];
     }
     __syncthreads();
     float* key = a.keys + (((int64_t)l * a.capacity_groups + t) * H + h) * d;
-    for (int c = tid; c < d; c += kBlock) {
+    for (int q = tid; q < d; q += kBlock) {
         double sum = 0.0;
-        for (int r = 0; r < rpp; ++r) sum += shared_buf[r * d + c];
-        key[c] = (float)(sum / (double)G);
+        for (int r = 0; r < rpp; ++r) sum += shared_buf[r * d + q];
+        key[(q % lpr) * 8 + q / lpr] = (float)(sum / (double)G);
     }
 }
 

@@ -95,14 +95,15 @@ __global__ void __launch_bounds__(kBlock) query_fold_kernel(const ScoreArgs a, c
     __shared__ double wsum[kBlock / 64];
     if (active) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) red[jl * d + slot * 8 + i] = acc[i];
+        for (int i = 0; i < 8; ++i) red[jl * d + i * lpr + slot] = acc[i];  // position order: no bank conflicts
     }
     __syncthreads();
     double sq = 0.0;
-    for (int c = tid; c < d; c += kBlock) {
+    for (int p = tid; p < d; p += kBlock) {  // position p = i * lpr + slot holds channel slot * 8 + i
         double sum = 0.0;
-        for (int j = 0; j < jn; ++j) sum += red[j * d + c];
+        for (int j = 0; j < jn; ++j) sum += red[j * d + p];
         const double qb = sum * (1.0 / (double)Tq);
+        const int c = (p % lpr) * 8 + p / lpr;
         a.ws_qbar[(int64_t)li * HD + (int64_t)h * d + c] = qb;
         sq += qb * qb;
     }
