@@ -159,7 +159,13 @@ __global__ void __launch_bounds__(kBlock) score_mean_query_kernel(const ScoreArg
     };
     load_keys(0);
 
-    for (int e = tid; e < HD; e += kBlock) qbar[e] = a.ws_qbar[(int64_t)li * HD + e];
+    // q-bar is staged so that the 16 lanes of a frame-group read consecutive 16-byte pairs:
+    // element e = 64c + 4s + i (chunk c, lane s, i < 4) sits at ((2c + i/2) * 16 + s) * 2 + i%2
+    // (in element order the lanes' pairs would be 32 bytes apart: bank conflicts on every read)
+    for (int e = tid; e < HD; e += kBlock) {
+        const int c = e >> 6, sl = (e >> 2) & 15, i = e & 3;
+        qbar[(((2 * c + (i >> 1)) * 16 + sl) << 1) + (i & 1)] = a.ws_qbar[(int64_t)li * HD + e];
+    }
     double nq2 = 0.0;
     for (int hh = 0; hh < a.n_kv_heads; ++hh) nq2 += a.ws_qnorm2[(int64_t)li * a.n_kv_heads + hh];
     const double nq = sqrt(nq2);
@@ -178,7 +184,8 @@ __global__ void __launch_bounds__(kBlock) score_mean_query_kernel(const ScoreArg
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const double kd = (double)cur[c][i];
-                    dot = fma(qbar[e + i], kd, dot);
+                    const double qv = qbar[(((2 * ((e0 >> 6) + c) + (i >> 1)) * 16 + sub) << 1) + (i & 1)];
+                    dot = fma(qv, kd, dot);
                     nk2 = fma(kd, kd, nk2);
                 }
             }
@@ -366,7 +373,8 @@ hipError_t launch_score_mean_query(const ScoreArgs& a, hipStream_t s) {
     if (a.n_layers == 0 || a.n_groups == 0) return hipSuccess;
     const int per_block = kBlock / 16;
     const dim3 grid((a.n_groups + per_block - 1) / per_block, a.n_layers);
-    const size_t lds = (size_t)a.n_kv_heads * a.head_dim * sizeof(double);
+    // q-bar, padded to whole 64-element chunks (the staged order permutes within a chunk)
+    const size_t lds = (size_t)((a.n_kv_heads * a.head_dim + 63) / 64 * 64) * sizeof(double);
     score_mean_query_kernel<<<grid, dim3(kBlock), lds, s>>>(a);
     return hipGetLastError();
 }
