@@ -38,7 +38,11 @@
  *   - dequantized value = float32(code * s + m) with a single rounding
  *   - s < FLT_MIN (incl. max == min)  =>  s stored as 0, all codes 0
  *   - m = min + 0.0f so that a stored zero point is never -0
- *   - scale / zero stored as float32
+ *   - scale / zero stored as float32; meta_dtype = bfloat16 is a storage variant the paper
+ *     does not describe (the paper only says the memory keeps non-quantized parts in 16
+ *     bits): s and m are rounded to bfloat16 (nearest even) BEFORE the codes are computed,
+ *     the codes are taken against the rounded pair (so quantizer and dequantizer agree)
+ *     and the clamp to [0, levels] does real work (m may now lie above the minimum)
  *   - even channel -> low bits of the byte (little-endian nibbles)
  *   - quantization axis: the paper reduces over the G tokens of a channel
  *     (QAXIS_TOKENS); the benchmark configurations reduce over gs consecutive
@@ -81,6 +85,7 @@ typedef struct {
     int32_t in_dtype;        /* dtype of K/V handed to quantize       */
     int32_t out_dtype;       /* dtype of the active KV buffer         */
     int32_t sim;             /* TOMREF_SIM_*                          */
+    int32_t meta_dtype;      /* TOMREF_F32 or TOMREF_BF16: precision scale / zero are kept in */
 } tomref_config;
 
 /* ------------------------------------------------------------------ */
@@ -199,7 +204,7 @@ int32_t tomref_k_from_budget(int64_t budget_tokens, int32_t G, int64_t stored_to
 
 /* Eq. 9 on one quant-group: n values x[0], x[stride], ...  Writes the group's
  * scale and zero point and n unpacked codes c[0], c[cstride], ... */
-static void quant_group(const float* x, int64_t stride, int n, int levels,
+static void quant_group(const float* x, int64_t stride, int n, int levels, int meta_dtype,
                         float* scale, float* zero, uint8_t* c, int64_t cstride) {
     float mn = x[0], mx = x[0];
     for (int i = 1; i < n; ++i) {
@@ -210,7 +215,12 @@ static void quant_group(const float* x, int64_t stride, int n, int levels,
     mn = mn + 0.0f;                                 /* -0 -> +0 */
     float s = (mx - mn) / (float)levels;            /* Eq. 9: (max - min) / 15 for 4 bits */
     float inv;
-    if (!(s >= FLT_MIN)) { s = 0.0f; inv = 0.0f; }  /* flat or sub-normal range */
+    if (!(s >= FLT_MIN)) s = 0.0f;                  /* flat or sub-normal range */
+    if (meta_dtype == TOMREF_BF16) {                /* kept in 16 bits: round first, then use */
+        s = bf16_to_f32(f32_to_bf16(s));
+        mn = bf16_to_f32(f32_to_bf16(mn));
+    }
+    if (!(s >= FLT_MIN)) { s = 0.0f; inv = 0.0f; }
     else inv = 1.0f / s;
     *scale = s;
     *zero = mn;                                     /* Eq. 9: m = min */
@@ -238,12 +248,14 @@ int64_t tomref_code_bytes_per_tile(int32_t G, int32_t d, int32_t bits) {
 /* Quantize one head tile x[G][d].
  *   unpacked[G][d]  codes, one per byte (may be NULL)
  *   packed[G][d*bits/8]  channel 2j (4-bit) / 4j (2-bit) in the low bits of byte j
- *   scale/zero: HEAD_DIM -> [G][d/gs]; TOKENS -> [d]
+ *   scale/zero: HEAD_DIM -> [G][d/gs]; TOKENS -> [d]; float32 arrays that hold, with
+ *               meta_dtype bfloat16, values already rounded to bfloat16
  * Returns 0, or -1 on a shape the definition does not cover. */
 int32_t tomref_quantize_tile(const float* x, int32_t G, int32_t d, int32_t gs, int32_t qaxis,
-                             int32_t bits, uint8_t* unpacked, uint8_t* packed,
+                             int32_t bits, int32_t meta_dtype, uint8_t* unpacked, uint8_t* packed,
                              float* scale, float* zero) {
     if (G < 1 || d < 1 || (bits != 4 && bits != 2)) return -1;
+    if (meta_dtype != TOMREF_F32 && meta_dtype != TOMREF_BF16) return -1;
     int per_byte = 8 / bits;
     if (d % per_byte) return -1;
     if (qaxis == TOMREF_QAXIS_HEAD_DIM && (gs < 1 || d % gs)) return -1;
@@ -255,13 +267,13 @@ int32_t tomref_quantize_tile(const float* x, int32_t G, int32_t d, int32_t gs, i
         int ng = d / gs;
         for (int tok = 0; tok < G; ++tok)
             for (int g = 0; g < ng; ++g)
-                quant_group(x + (int64_t)tok * d + g * gs, 1, gs, levels,
+                quant_group(x + (int64_t)tok * d + g * gs, 1, gs, levels, meta_dtype,
                             &scale[(int64_t)tok * ng + g], &zero[(int64_t)tok * ng + g],
                             c + (int64_t)tok * d + g * gs, 1);
     } else {
         /* paper Eq. 9: one (scale, zero) per channel, over the G tokens */
         for (int ch = 0; ch < d; ++ch)
-            quant_group(x + ch, d, G, levels, &scale[ch], &zero[ch], c + ch, d);
+            quant_group(x + ch, d, G, levels, meta_dtype, &scale[ch], &zero[ch], c + ch, d);
     }
     if (unpacked) memcpy(unpacked, c, (size_t)G * d);
     if (packed) {
@@ -318,6 +330,7 @@ static int config_ok(const tomref_config* c) {
     if (c->n_q_heads % c->n_kv_heads) return 0;
     if (c->group_tokens < 1 || c->capacity_groups < 1) return 0;
     if (c->bits != 4 && c->bits != 2) return 0;
+    if (c->meta_dtype != TOMREF_F32 && c->meta_dtype != TOMREF_BF16) return 0;
     if (c->head_dim % (8 / c->bits)) return 0;
     if (c->qaxis == TOMREF_QAXIS_HEAD_DIM) {
         if (c->qgroup < 1 || c->head_dim % c->qgroup) return 0;
@@ -367,7 +380,7 @@ int32_t tomref_quantize_append(const tomref_config* cfg, uint8_t* codes, float* 
                             x[(int64_t)tok * d + ch] =
                                 load_elem(src, cfg->in_dtype, base + tok * strides[3] + ch);
                     const int64_t ti = tile_index(cfg, l, kv, t, h);
-                    tomref_quantize_tile(x, G, d, cfg->qgroup, cfg->qaxis, cfg->bits, NULL,
+                    tomref_quantize_tile(x, G, d, cfg->qgroup, cfg->qaxis, cfg->bits, cfg->meta_dtype, NULL,
                                          codes + ti * cb, scale + ti * mt, zero + ti * mt);
                 }
                 for (int tok = 0; tok < G; ++tok)

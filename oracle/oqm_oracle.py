@@ -36,7 +36,7 @@ def build(force: bool = False) -> str:
 class Config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "n_layers", "n_kv_heads", "n_q_heads", "head_dim", "group_tokens", "qgroup",
-        "qaxis", "bits", "capacity_groups", "in_dtype", "out_dtype", "sim")]
+        "qaxis", "bits", "capacity_groups", "in_dtype", "out_dtype", "sim", "meta_dtype")]
 
 
 @dataclass
@@ -75,7 +75,7 @@ def lib():
         L.tomref_meta_per_tile.restype = i64
         L.tomref_code_bytes_per_tile.argtypes = [i32, i32, i32]
         L.tomref_code_bytes_per_tile.restype = i64
-        L.tomref_quantize_tile.argtypes = [f32p, i32, i32, i32, i32, i32, vp, vp, f32p, f32p]
+        L.tomref_quantize_tile.argtypes = [f32p, i32, i32, i32, i32, i32, i32, vp, vp, f32p, f32p]
         L.tomref_quantize_tile.restype = i32
         L.tomref_dequant_tile.argtypes = [vp, f32p, f32p, i32, i32, i32, i32, i32, f32p]
         L.tomref_dequant_tile.restype = i32
@@ -143,7 +143,8 @@ def k_from_budget(budget_tokens, G, stored_tokens) -> int:
 
 
 # ---------------------------------------------------------------- tile level
-def quantize_tile(x: np.ndarray, gs: int, qaxis: int = QAXIS_HEAD_DIM, bits: int = 4):
+def quantize_tile(x: np.ndarray, gs: int, qaxis: int = QAXIS_HEAD_DIM, bits: int = 4,
+                  meta_dtype: int = F32):
     """x: float32 [G][d] -> (unpacked [G][d] u8, packed [G][d*bits/8] u8, scale, zero)."""
     x = np.ascontiguousarray(x, np.float32)
     G, d = x.shape
@@ -152,7 +153,7 @@ def quantize_tile(x: np.ndarray, gs: int, qaxis: int = QAXIS_HEAD_DIM, bits: int
     packed = np.empty((G, d * bits // 8), np.uint8)
     scale = np.empty(nm, np.float32)
     zero = np.empty(nm, np.float32)
-    rc = lib().tomref_quantize_tile(_p(x), G, d, gs, qaxis, bits, _p(unpacked), _p(packed),
+    rc = lib().tomref_quantize_tile(_p(x), G, d, gs, qaxis, bits, meta_dtype, _p(unpacked), _p(packed),
                                     _p(scale), _p(zero))
     if rc != 0:
         raise ValueError("tomref_quantize_tile: bad shape")
@@ -182,9 +183,9 @@ def summary_key(x: np.ndarray) -> np.ndarray:
 # ---------------------------------------------------------------- the four calls
 def make_config(n_layers, n_kv_heads, n_q_heads, head_dim, group_tokens, qgroup,
                 capacity_groups, qaxis=QAXIS_HEAD_DIM, bits=4, in_dtype=BF16, out_dtype=BF16,
-                sim=SIM_COSINE) -> Config:
+                sim=SIM_COSINE, meta_dtype=F32) -> Config:
     return Config(n_layers, n_kv_heads, n_q_heads, head_dim, group_tokens, qgroup, qaxis, bits,
-                  capacity_groups, in_dtype, out_dtype, sim)
+                  capacity_groups, in_dtype, out_dtype, sim, meta_dtype)
 
 
 def new_store(cfg: Config) -> Store:

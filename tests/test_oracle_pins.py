@@ -125,6 +125,53 @@ def test_quantize_tile_equals_torch_expression(oracle, G, d, gs, bits):
     assert np.array_equal(zero.view(np.uint32), tz.view(np.uint32))
 
 
+@pytest.mark.parametrize("G,d,gs,bits,qaxis", [(16, 64, 32, 4, 0), (9, 128, 64, 2, 0), (50, 64, 64, 4, 1),
+                                               (7, 32, 8, 2, 1)])
+def test_bf16_metadata_variant(oracle, G, d, gs, bits, qaxis):
+    """scale / zero kept in bfloat16: both are rounded (torch's own bfloat16 rounding) before
+    the codes are taken, the codes are taken against the rounded pair and clamped, and the
+    reconstruction stays within half a (rounded) step plus what the rounding of m and s moves."""
+    r = _rng(G * 31 + d + bits)
+    x = (r.standard_normal((G, d)) * r.uniform(0.1, 30) + r.uniform(-5, 5)).astype(np.float32)
+    if qaxis == 0:
+        x[0, :gs] = 1.25                                             # a flat quant-group
+    levels = (1 << bits) - 1
+    codes, packed, scale, zero = oracle.quantize_tile(x, gs, qaxis, bits, oracle.BF16)
+    # library-routine statement
+    t = torch.from_numpy(x)
+    t = t.view(G, d // gs, gs) if qaxis == 0 else t.t().contiguous().view(d, 1, G)
+    mn = t.amin(-1, keepdim=True) + 0.0
+    mx = t.amax(-1, keepdim=True)
+    s = (mx - mn) / float(levels)
+    s = torch.where(s >= torch.finfo(torch.float32).tiny, s, torch.zeros_like(s))
+    s = s.to(torch.bfloat16).float()
+    m = mn.to(torch.bfloat16).float()
+    ok = s >= torch.finfo(torch.float32).tiny
+    inv = torch.where(ok, 1.0 / torch.where(ok, s, torch.ones_like(s)), torch.zeros_like(s))
+    c = torch.clamp(torch.round((t - m).double() * inv.double()), 0, levels).to(torch.uint8)
+    if qaxis == 0:
+        c, s_, m_ = c.view(G, d).numpy(), s.view(G, d // gs).numpy(), m.view(G, d // gs).numpy()
+        step = np.repeat(s_, gs, axis=1)
+        zpt = np.repeat(m_, gs, axis=1)
+    else:
+        c, s_, m_ = c.view(d, G).t().contiguous().numpy(), s.view(d).numpy(), m.view(d).numpy()
+        step = np.broadcast_to(s_, (G, d))
+        zpt = np.broadcast_to(m_, (G, d))
+    assert np.array_equal(codes, c)
+    assert np.array_equal(scale.view(np.uint32), s_.view(np.uint32))
+    assert np.array_equal(zero.view(np.uint32), m_.view(np.uint32))
+    # representable in 16 bits
+    assert np.all(scale.view(np.uint32) & 0xFFFF == 0) and np.all(zero.view(np.uint32) & 0xFFFF == 0)
+    # the rounding moved scale and zero by at most half a bfloat16 ulp
+    _, _, s32, m32 = oracle.quantize_tile(x, gs, qaxis, bits, oracle.F32)
+    assert np.all(np.abs(scale - s32) <= np.abs(s32) * 2.0 ** -8) and np.all(np.abs(zero - m32) <= np.abs(m32) * 2.0 ** -8)
+    # reconstruction: half a step, plus the shift of the zero point, plus the top code's stretch
+    xh = oracle.dequant_tile(packed, scale, zero, G, d, gs, qaxis, bits)
+    bound = 0.5 * step * (1 + 1e-5) + 2.0 ** -8 * (np.abs(zpt) + levels * step) + 1e-6
+    assert np.all(np.abs(xh - x) <= bound)
+    assert codes.max() <= levels
+
+
 def test_quantize_invariants(oracle):
     r = _rng(11)
     G, d, gs = 33, 128, 64
