@@ -26,15 +26,15 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
 METRIC = "OQM quantize-append + retrieve/dequant HBM GB/s (% of peak); retrieval ms/query"
 
 
-def bytes_append(w, n_frames, in_bytes, bits=4):
+def bytes_append(w, n_frames, in_bytes, bits=4, meta_b=8):
     e = n_frames * w.n_layers * 2 * w.n_kv_heads * w.group_tokens * w.head_dim
     keys = n_frames * w.n_layers * w.n_kv_heads * w.head_dim * 4
-    return e * in_bytes + e * bits // 8 + (e // w.qgroup) * 8 + keys, e
+    return e * in_bytes + e * bits // 8 + (e // w.qgroup) * meta_b + keys, e
 
 
-def bytes_gather(w, k_eff, out_bytes, bits=4):
+def bytes_gather(w, k_eff, out_bytes, bits=4, meta_b=8):
     e = w.n_layers * k_eff * 2 * w.n_kv_heads * w.group_tokens * w.head_dim
-    return e * bits // 8 + (e // w.qgroup) * 8 + e * out_bytes + w.n_layers * k_eff * 4, e
+    return e * bits // 8 + (e // w.qgroup) * meta_b + e * out_bytes + w.n_layers * k_eff * 4, e
 
 
 def bytes_score(w, T, q_bytes):
@@ -61,7 +61,7 @@ def measured_traffic(kernel, workload):
     return None
 
 
-def cpu_baseline(w, batches_cpu, q_cpu, threads, qaxis=0, bits=4):
+def cpu_baseline(w, batches_cpu, q_cpu, threads, qaxis=0, bits=4, meta="f32"):
     """The oracle, as it stands, on a bounded sample of the same workload: the given append
     batches (all layers) and one retrieval over what they stored.  Threads split layers."""
     from concurrent.futures import ThreadPoolExecutor
@@ -75,7 +75,7 @@ def cpu_baseline(w, batches_cpu, q_cpu, threads, qaxis=0, bits=4):
     F = sum(b[0].shape[0] for b in batches_cpu)
     cfg = orc.make_config(w.n_layers, w.n_kv_heads, w.n_q_heads, w.head_dim, w.group_tokens,
                           w.qgroup, F, qaxis=qaxis, bits=bits, in_dtype=dt, out_dtype=dt,
-                          sim=1 if w.sim == "cosine" else 0)
+                          sim=1 if w.sim == "cosine" else 0, meta_dtype=1 if meta == "bf16" else 0)
     st = orc.new_store(cfg)
     L = w.n_layers
     threads = max(1, min(threads, L))
@@ -110,8 +110,9 @@ def cpu_baseline(w, batches_cpu, q_cpu, threads, qaxis=0, bits=4):
         list(ex.map(layer_job, range(L)))
     dtm = time.perf_counter() - t0
     eb = 4 if w.dtype == "f32" else 2
-    ba, ea = bytes_append(w, F, eb, bits)
-    bg, eg = bytes_gather(w, k_eff, eb, bits)
+    mb = 4 if meta == "bf16" else 8
+    ba, ea = bytes_append(w, F, eb, bits, mb)
+    bg, eg = bytes_gather(w, k_eff, eb, bits, mb)
     total = ba + bg + bytes_score(w, F, eb) + bytes_topk(w, F, k_eff)
     return {"value": total / dtm / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
             "sample": f"{F} frames x {L} layers appended ({len(kb)} calls) + 1 query "
@@ -131,6 +132,8 @@ def main():
                     help="tokens = the paper's Eq. 9 (scale/zero per channel over the G tokens)")
     ap.add_argument("--group-tokens", type=int, default=0, help="override G (the paper keeps 50)")
     ap.add_argument("--bits", type=int, default=4, choices=[4, 2], help="code width (2 = the paper's ablation)")
+    ap.add_argument("--meta", default="f32", choices=["f32", "bf16"],
+                    help="precision scale / zero are kept in (bf16 = storage variant, half the metadata)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-batches", type=int, default=32,
                     help="append calls the oracle is timed on (32 x 32 frames = the whole C3 stream)")
@@ -160,6 +163,7 @@ def main():
     cfg = oqm.make_config(w.n_layers, w.n_kv_heads, w.n_q_heads, w.head_dim, w.group_tokens,
                           w.qgroup, T, qaxis=oqm.TOM_QAXIS_TOKENS if tok else oqm.TOM_QAXIS_HEAD_DIM,
                           bits=args.bits, in_dtype=dtc, out_dtype=dtc,
+                          meta_dtype=oqm.TOM_BF16 if args.meta == "bf16" else oqm.TOM_F32,
                           sim=oqm.TOM_SIM_COSINE if w.sim == "cosine" else oqm.TOM_SIM_DOT)
     mem = oqm.Memory.allocate(cfg, dev)
     if tok:   # byte model: one (scale, zero) pair per channel and tile instead of per gs elements
@@ -167,7 +171,8 @@ def main():
     L = w.n_layers
 
     # distinct input batches, more than the 256 MB last-level cache can hold, rotated per step
-    batch_bytes = bytes_append(w, fpa, eb, args.bits)[0]
+    meta_b = 4 if args.meta == "bf16" else 8
+    batch_bytes = bytes_append(w, fpa, eb, args.bits, meta_b)[0]
     n_batches = max(2, min(T // fpa, int(3.0e9 // max(batch_bytes, 1)) or 1, 64))
     batches = [synth_kv.kv_frames(w, i * fpa, fpa, dev) for i in range(n_batches)]
     queries = [synth_kv.query(w, i, dev) for i in range(4)]
@@ -291,9 +296,10 @@ def main():
 
     ms_append, ms_score, ms_topk, ms_gather = avg_ms(0, 1), avg_ms(1, 2), avg_ms(2, 3), avg_ms(3, 4)
     ms_step = wall * 1e3 / args.steps
-    b_app, e_app = bytes_append(w, fpa, eb, args.bits)
-    b_gat, e_gat = bytes_gather(w, k_eff, eb, args.bits)
-    default_variant = not tok and args.bits == 4 and not args.group_tokens and not args.frames_per_append
+    b_app, e_app = bytes_append(w, fpa, eb, args.bits, meta_b)
+    b_gat, e_gat = bytes_gather(w, k_eff, eb, args.bits, meta_b)
+    default_variant = (not tok and args.bits == 4 and not args.group_tokens and not args.frames_per_append
+                       and args.meta == "f32")
     b_sc, b_tk = bytes_score(w, T, eb), bytes_topk(w, T, k_eff)
     total_bytes = b_app + b_gat + b_sc + b_tk
     gbps = lambda b, ms: b / (ms * 1e-3) / 1e9
@@ -310,7 +316,7 @@ def main():
         "config": {
             "workload": f"{w.name}: {L} layers, {w.n_kv_heads} KV heads ({w.n_q_heads} query heads), "
                         f"head_dim {w.head_dim}, {w.dtype} K/V, {T} frames x {w.group_tokens} tokens stored, "
-                        f"{fpa} frames per quantize-append, {args.bits}-bit codes, "
+                        f"{fpa} frames per quantize-append, {args.bits}-bit codes, {args.meta} scale/zero, "
                         + (f"scale/zero per channel over the {w.group_tokens} tokens, " if tok else
                            f"quant-group {w.qgroup} over head_dim, ") +
                         ""
@@ -361,7 +367,7 @@ def main():
         host = [(k.cpu(), v.cpu()) for k, v in batches[:min(nb, n_batches)]]
         sample = [host[i % len(host)] for i in range(nb)]      # cycle the resident batches
         threads = min(16, os.cpu_count() or 1)
-        out["cpu_baseline"] = cpu_baseline(w, sample, queries[0].cpu(), threads, 1 if tok else 0, args.bits)
+        out["cpu_baseline"] = cpu_baseline(w, sample, queries[0].cpu(), threads, 1 if tok else 0, args.bits, args.meta)
         out["cpu_baseline"]["value"] = round(out["cpu_baseline"]["value"], 3)
         del out["cpu_baseline"]["tokens_per_s_append"]
     print(json.dumps(out))

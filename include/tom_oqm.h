@@ -34,7 +34,8 @@
  *   codes  [L][2 (0 = K, 1 = V)][T_cap][H_k][G][d * bits / 8]   uint8
  *          4-bit: channel 2j in the low nibble of byte j, channel 2j+1 in the high nibble
  *          2-bit: channel 4j + u in bits [2u, 2u + 2) of byte j
- *   meta   (scale, zero) pairs, scale first
+ *   meta   (scale, zero) pairs, scale first; float32 each, or with cfg.meta_dtype = TOM_BF16
+ *          bfloat16 each (one 32-bit word per pair, scale in the low half)
  *          qaxis HEAD_DIM: [L][2][T_cap][H_k][G][d / gs][2]      float32
  *          qaxis TOKENS  : [L][2][T_cap][H_k][d][2]              float32
  *   keys   [L][T_cap][H_k][d]                                    float32 (summary keys)
@@ -97,6 +98,7 @@ typedef struct {
     int32_t in_dtype;        /* tom_dtype_t of K/V handed to quantize_append             */
     int32_t out_dtype;       /* tom_dtype_t of the active KV buffer                      */
     int32_t sim;             /* tom_sim_t                                                */
+    int32_t meta_dtype;      /* TOM_F32, or TOM_BF16: (scale, zero) kept as bfloat16 pairs */
 } tom_oqm_config_t;
 
 typedef struct {
@@ -150,6 +152,10 @@ int32_t tom_oqm_k_from_budget(int64_t budget_tokens, int32_t group_tokens, int32
  * not rounded before the rounding to an integer; s below FLT_MIN (e.g.
  * max == min) is stored as 0 with all codes 0; m is stored as +0 rather than
  * -0.  K and V use the same quantizer.
+ * With meta_dtype TOM_BF16 (a storage variant; halves the metadata) s and m are rounded
+ * to bfloat16, nearest even, right after the "below FLT_MIN" rule; the codes are then
+ * taken against the rounded pair, so the clamp does real work and the reconstruction
+ * error is at most s/2 + 2^-8 (|m| + n s).  |m| above the largest bfloat16 is unspecified.
  * Also writes one summary key per (layer, frame-group, KV head): the mean over
  * the G tokens of the un-quantized keys (accumulated in float64, rounded once).
  *

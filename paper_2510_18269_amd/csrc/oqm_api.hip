@@ -42,6 +42,10 @@ static tom_status_t check_config(const tom_oqm_config_t* c) {
     if (c->sim != TOM_SIM_DOT && c->sim != TOM_SIM_COSINE)
         return fail(TOM_ERR_INVALID_ARG, "sim must be TOM_SIM_DOT or TOM_SIM_COSINE");
     if (c->bits != 4 && c->bits != 2) return fail(TOM_ERR_INVALID_ARG, "bits must be 4 or 2");
+    if (c->meta_dtype == TOM_F16)
+        return fail(TOM_ERR_UNSUPPORTED, "meta_dtype TOM_F16: binary16 cannot hold the scale of wide groups; use TOM_BF16");
+    if (c->meta_dtype != TOM_F32 && c->meta_dtype != TOM_BF16)
+        return fail(TOM_ERR_INVALID_ARG, "meta_dtype must be TOM_F32 or TOM_BF16");
     if (c->qaxis != TOM_QAXIS_HEAD_DIM && c->qaxis != TOM_QAXIS_TOKENS)
         return fail(TOM_ERR_INVALID_ARG, "qaxis is not a tom_qaxis_t");
     if (c->qaxis == TOM_QAXIS_HEAD_DIM) {
@@ -77,7 +81,7 @@ tom_status_t tom_oqm_query_sizes(const tom_oqm_config_t* cfg, tom_oqm_sizes_t* s
     const Layout lay = layout_of(*cfg);
     const size_t tiles = (size_t)cfg->n_layers * 2 * (size_t)cfg->capacity_groups * cfg->n_kv_heads;
     sizes->codes = tiles * (size_t)lay.tile_code_bytes;
-    sizes->meta = tiles * (size_t)lay.tile_meta * 2 * sizeof(float);
+    sizes->meta = tiles * (size_t)lay.tile_meta * 2 * (cfg->meta_dtype == TOM_BF16 ? 2 : sizeof(float));
     sizes->keys = (size_t)cfg->n_layers * cfg->capacity_groups * cfg->n_kv_heads * cfg->head_dim *
                   sizeof(float);
     return TOM_OK;
@@ -101,7 +105,7 @@ tom_status_t tom_oqm_bind(tom_oqm_t* h, void* codes, void* meta, void* keys) {
     if (!aligned16(codes) || !aligned16(meta) || !aligned16(keys))
         return fail(TOM_ERR_INVALID_ARG, "storage arrays must be 16-byte aligned");
     h->codes = static_cast<uint8_t*>(codes);
-    h->meta = static_cast<float*>(meta);
+    h->meta = meta;
     h->keys = static_cast<float*>(keys);
     h->bound = true;
     return TOM_OK;
@@ -183,6 +187,7 @@ tom_status_t tom_oqm_quantize_append(tom_oqm_t* h, int32_t layer0, int32_t n_lay
     a.first_group = h->n_groups;
     a.qaxis = c.qaxis;
     a.bits = c.bits;
+    a.meta_bf16 = c.meta_dtype == TOM_BF16;
     const hipError_t e = launch_quantize_append(a, c.in_dtype, static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return fail(TOM_ERR_HIP, "quantize_append launch: %s", hipGetErrorString(e));
     if (commit) h->n_groups += n_frames;
@@ -342,6 +347,7 @@ static tom_status_t assemble_impl(const tom_oqm_t* h, int32_t layer0, int32_t n_
     a.n_groups = h->n_groups;
     a.qaxis = c.qaxis;
     a.bits = c.bits;
+    a.meta_bf16 = c.meta_dtype == TOM_BF16;
     a.prefix_rows = prefix_rows;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     if (copy_prefix) {

@@ -10,7 +10,7 @@
 struct tom_oqm {
     tom_oqm_config_t cfg;
     uint8_t* codes = nullptr;
-    float* meta = nullptr;  // (scale, zero) pairs
+    void* meta = nullptr;   // (scale, zero) pairs: float32 x 2, or bfloat16 x 2 (cfg.meta_dtype)
     float* keys = nullptr;
     int32_t n_groups = 0;
     bool bound = false;
@@ -46,17 +46,18 @@ struct QuantArgs {
     const void* ksum;  // source of the summary key (== k unless the caller gave another)
     int64_t stride_frame, stride_layer, stride_head, stride_token;  // elements
     uint8_t* codes;
-    float* meta;  // [..][G][d/gs][2]: (scale, zero) pairs
+    void* meta;   // [..][G][d/gs][2]: (scale, zero) pairs, float32 or bfloat16
     float* keys;
     int32_t n_kv_heads, head_dim, group_tokens, qgroup, capacity_groups;
     int32_t layer0, n_layers, n_frames, first_group;
     int32_t qaxis;
     int32_t bits;  // 4 or 2
+    int32_t meta_bf16;  // (scale, zero) stored as bfloat16 pairs
 };
 
 struct DequantArgs {
     const uint8_t* codes;
-    const float* meta;
+    const void* meta;
     const int32_t* idx;  // [n_layers][k]
     void* k_out;
     void* v_out;
@@ -64,6 +65,7 @@ struct DequantArgs {
     int32_t layer0, n_layers, k, k_eff, n_groups;
     int32_t qaxis;
     int32_t bits;         // 4 or 2
+    int32_t meta_bf16;    // (scale, zero) stored as bfloat16 pairs
     int32_t prefix_rows;  // rows of each head's active buffer that precede the gathered groups
 };
 

@@ -20,7 +20,7 @@ namespace {
 
 // kUnroll: rows per lane whose loads are issued before any is converted; the host picks it
 // so that a whole tile is covered in one trip when it fits (13 trips of 16 rows for 196 x 128).
-template <typename OUT, int kUnroll, bool TOKEN_AXIS, int BITS>
+template <typename OUT, int kUnroll, bool TOKEN_AXIS, int BITS, bool MB>
 __global__ void __launch_bounds__(kBlock) dequant_gather_kernel(const DequantArgs a, const int lpg) {
     constexpr int EB = elem_bytes<OUT>::value;
     constexpr uint32_t CW = BITS;          // bytes of packed codes per lane and row (8 channels)
@@ -45,12 +45,13 @@ __global__ void __launch_bounds__(kBlock) dequant_gather_kernel(const DequantArg
     const int64_t tile = (((int64_t)(a.layer0 + li) * 2 + kv) * a.capacity_groups + t) * H + h;
     const char* codes_t = reinterpret_cast<const char*>(a.codes + tile * ((int64_t)G * d * BITS / 8));
     // token axis (Eq. 9): one pair per channel, d pairs per tile; else G * d/gs pairs
-    const f32x2* meta_t =
-        reinterpret_cast<const f32x2*>(a.meta) + tile * (TOKEN_AXIS ? (int64_t)d : (int64_t)G * ng);
+    typedef typename MetaPair<MB>::type meta_pair;  // two float32, or two bfloat16 in one word
+    const meta_pair* meta_t =
+        reinterpret_cast<const meta_pair*>(a.meta) + tile * (TOKEN_AXIS ? (int64_t)d : (int64_t)G * ng);
     f32x2 ch[8];  // token axis: the pairs of this lane's 8 channels, loaded once
     if (TOKEN_AXIS) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) ch[i] = meta_t[slot * 8 + i];
+        for (int i = 0; i < 8; ++i) ch[i] = widen_pair(meta_t[slot * 8 + i]);
     }
     const int64_t head_rows = (int64_t)a.prefix_rows + (int64_t)a.k * G;  // rows per head buffer
     char* out = static_cast<char*>(kv ? a.v_out : a.k_out) +
@@ -62,12 +63,12 @@ __global__ void __launch_bounds__(kBlock) dequant_gather_kernel(const DequantArg
 
     for (int r0 = 0; r0 + row0 < G; r0 += kUnroll * rpp) {
         uint32_t w[kUnroll];
-        f32x2 sm[kUnroll];
+        meta_pair sm[kUnroll];
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             const int rb = r0 + u * rpp;
             w[u] = 0u;
-            sm[u] = f32x2{0.0f, 0.0f};
+            sm[u] = meta_pair{};
             if (rb + row0 < G) {
                 w[u] = load_codes8<BITS>(codes_t + (code_lane + (uint32_t)rb * lpr * CW));
                 if (!TOKEN_AXIS) sm[u] = meta_t[meta_lane + rb * ng];
@@ -81,7 +82,7 @@ __global__ void __launch_bounds__(kBlock) dequant_gather_kernel(const DequantArg
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
                     const float c = (float)((w[u] >> (BITS * i)) & CMASK);
-                    const f32x2 p = TOKEN_AXIS ? ch[i] : sm[u];
+                    const f32x2 p = TOKEN_AXIS ? ch[i] : widen_pair(sm[u]);
                     x[i] = __builtin_fmaf(c, p[0], p[1]);  // Eq. 11, rounded once to float32
                 }
                 store8(out + (out_lane + (uint32_t)rb * d * EB), OUT{}, x);
@@ -111,14 +112,19 @@ hipError_t launch_t(const DequantArgs& a, hipStream_t s) {
     const int trips = (a.group_tokens + rpp - 1) / rpp;  // row passes per tile
     const int lpg = a.qgroup / 8;  // unused for the token axis
     const bool tok = a.qaxis == TOM_QAXIS_TOKENS;
-    auto go = [&](auto unroll, auto bits) {
+    auto go = [&](auto unroll, auto bits, auto mb) {
         constexpr int U = decltype(unroll)::value, B = decltype(bits)::value;
-        if (tok) dequant_gather_kernel<OUT, U, true, B><<<grid, block, 0, s>>>(a, 1);
-        else dequant_gather_kernel<OUT, U, false, B><<<grid, block, 0, s>>>(a, lpg);
+        constexpr bool M = decltype(mb)::value;
+        if (tok) dequant_gather_kernel<OUT, U, true, B, M><<<grid, block, 0, s>>>(a, 1);
+        else dequant_gather_kernel<OUT, U, false, B, M><<<grid, block, 0, s>>>(a, lpg);
+    };
+    auto with_meta = [&](auto unroll, auto bits) {
+        if (a.meta_bf16) go(unroll, bits, std::true_type{});
+        else go(unroll, bits, std::false_type{});
     };
     auto with_bits = [&](auto unroll) {
-        if (a.bits == 2) go(unroll, std::integral_constant<int, 2>{});
-        else go(unroll, std::integral_constant<int, 4>{});
+        if (a.bits == 2) with_meta(unroll, std::integral_constant<int, 2>{});
+        else with_meta(unroll, std::integral_constant<int, 4>{});
     };
     if (trips <= 4) with_bits(std::integral_constant<int, 4>{});
     else if (trips <= 8 || trips > 13) with_bits(std::integral_constant<int, 8>{});

@@ -210,6 +210,31 @@ __device__ __forceinline__ float rcp_scale(float s) {
     return rcp_exact(s);
 }
 
+// ---- (scale, zero) pairs as stored: two float32, or two bfloat16 in one 32-bit word -------
+template <bool BF16_META> struct MetaPair;
+template <> struct MetaPair<false> { typedef f32x2 type; };
+template <> struct MetaPair<true> { typedef uint32_t type; };
+
+// Rounds (s, m) to bfloat16 (nearest even, one v_cvt_pk_bf16_f32), returns the stored word
+// and replaces s and m by the rounded values, which is what the codes are then taken against.
+__device__ __forceinline__ uint32_t round_pair_bf16(float& s, float& m) {
+    const f32x2 v = {s, m};
+    const uint32_t w = __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+    s = __uint_as_float(w << 16);
+    m = __uint_as_float(w & 0xffff0000u);
+    return w;
+}
+__device__ __forceinline__ f32x2 widen_pair(f32x2 p) { return p; }
+__device__ __forceinline__ f32x2 widen_pair(uint32_t w) {
+    return f32x2{__uint_as_float(w << 16), __uint_as_float(w & 0xffff0000u)};
+}
+// code + 2^23 clamped to [2^23, 2^23 + levels]: needed once the zero point is no longer the
+// exact minimum (bfloat16 metadata); one v_med3_f32
+template <int BITS>
+__device__ __forceinline__ float clamp_code(float t) {
+    return __builtin_amdgcn_fmed3f(t, 8388608.0f, 8388608.0f + (float)((1 << BITS) - 1));
+}
+
 template <typename T> struct elem_bytes;
 template <> struct elem_bytes<In_f32> { static constexpr int value = 4; };
 template <> struct elem_bytes<In_bf16> { static constexpr int value = 2; };

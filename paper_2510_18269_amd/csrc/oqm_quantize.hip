@@ -27,7 +27,7 @@ namespace {
 
 constexpr int kUnroll = 2;  // token rows per lane and loop trip
 
-template <typename IN, int LPG, bool SEPARATE_SUMMARY, int BITS>
+template <typename IN, int LPG, bool SEPARATE_SUMMARY, int BITS, bool MB>
 __global__ void __launch_bounds__(kBlock) quantize_append_kernel(const QuantArgs a) {
     constexpr int EB = elem_bytes<IN>::value;
     constexpr uint32_t CW = BITS;  // bytes of packed codes per lane and row (8 channels)
@@ -55,7 +55,8 @@ __global__ void __launch_bounds__(kBlock) quantize_append_kernel(const QuantArgs
     const char* src = static_cast<const char*>(kv ? a.v : a.k) + in_off * EB;
     const int64_t tile = (((int64_t)l * 2 + kv) * a.capacity_groups + t) * H + h;
     char* codes_t = reinterpret_cast<char*>(a.codes + tile * ((int64_t)G * d * BITS / 8));
-    f32x2* meta_t = reinterpret_cast<f32x2*>(a.meta) + tile * ((int64_t)G * ng);
+    typedef typename MetaPair<MB>::type meta_pair;  // two float32, or two bfloat16 in one word
+    meta_pair* meta_t = reinterpret_cast<meta_pair*>(a.meta) + tile * ((int64_t)G * ng);
     const uint32_t in_row_bytes = (uint32_t)a.stride_token * EB;
     const uint32_t in_lane = (uint32_t)row0 * in_row_bytes + (uint32_t)slot * 8u * EB;
     const uint32_t code_lane = ((uint32_t)row0 * lpr + slot) * CW;
@@ -96,23 +97,20 @@ __global__ void __launch_bounds__(kBlock) quantize_append_kernel(const QuantArgs
             group_minmax<LPG>(mn, mx);
             mn = mn + 0.0f;  // never store -0 as a zero point
             float s = div_levels_exact<BITS>(__fsub_rn(mx, mn));
-            float inv;
-            if (s >= 1.17549435e-38f) {
-                inv = rcp_scale<BITS>(s);
-            } else {  // flat or sub-normal range: all codes 0
-                s = 0.0f;
-                inv = 0.0f;
-            }
+            if (!(s >= 1.17549435e-38f)) s = 0.0f;  // flat or sub-normal range: all codes 0
+            meta_pair stored;
+            if constexpr (MB) stored = round_pair_bf16(s, mn);  // the codes follow the rounded pair
+            const float inv = s >= 1.17549435e-38f ? rcp_scale<BITS>(s) : 0.0f;
+            if constexpr (!MB) stored = f32x2{s, mn};
             float tq[8];
 #pragma unroll
-            for (int i = 0; i < 8; ++i)
+            for (int i = 0; i < 8; ++i) {
                 tq[i] = __builtin_fmaf(__fsub_rn(x[i], mn), inv, 8388608.0f);
+                if constexpr (MB) tq[i] = clamp_code<BITS>(tq[i]);  // m may lie above the minimum
+            }
             if (ok) {
                 store_codes8<BITS>(codes_t + (code_lane + (uint32_t)rb * lpr * CW), tq);
-                if (meta_writer) {
-                    const f32x2 sm = {s, mn};
-                    meta_t[meta_lane + rb * ng] = sm;
-                }
+                if (meta_writer) meta_t[meta_lane + rb * ng] = stored;
                 if (!SEPARATE_SUMMARY && do_sum) {
 #pragma unroll
                     for (int i = 0; i < 8; ++i) acc[i] += (double)x[i];
@@ -161,20 +159,21 @@ __global__ void __launch_bounds__(kBlock) quantize_append_kernel(const QuantArgs
     }
 }
 
-template <typename IN, int LPG, int BITS>
+template <typename IN, int LPG, int BITS, bool MB>
 hipError_t launch_b(const QuantArgs& a, hipStream_t s) {
     const dim3 grid(a.n_kv_heads, 2 * a.n_layers, a.n_frames);
     if (a.ksum != a.k)
-        quantize_append_kernel<IN, LPG, true, BITS><<<grid, dim3(kBlock), 0, s>>>(a);
+        quantize_append_kernel<IN, LPG, true, BITS, MB><<<grid, dim3(kBlock), 0, s>>>(a);
     else
-        quantize_append_kernel<IN, LPG, false, BITS><<<grid, dim3(kBlock), 0, s>>>(a);
+        quantize_append_kernel<IN, LPG, false, BITS, MB><<<grid, dim3(kBlock), 0, s>>>(a);
     return hipGetLastError();
 }
 
 template <typename IN, int LPG>
 hipError_t launch_t(const QuantArgs& a, hipStream_t s) {
     if (a.n_frames == 0 || a.n_layers == 0) return hipSuccess;
-    return a.bits == 2 ? launch_b<IN, LPG, 2>(a, s) : launch_b<IN, LPG, 4>(a, s);
+    if (a.meta_bf16) return a.bits == 2 ? launch_b<IN, LPG, 2, true>(a, s) : launch_b<IN, LPG, 4, true>(a, s);
+    return a.bits == 2 ? launch_b<IN, LPG, 2, false>(a, s) : launch_b<IN, LPG, 4, false>(a, s);
 }
 
 template <typename IN>

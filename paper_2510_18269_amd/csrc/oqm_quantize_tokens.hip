@@ -18,7 +18,7 @@ namespace {
 
 constexpr int kUnroll = 2;
 
-template <typename IN, bool SEPARATE_SUMMARY, int HOLD, int BITS>
+template <typename IN, bool SEPARATE_SUMMARY, int HOLD, int BITS, bool MB>
 __global__ void __launch_bounds__(kBlock) quantize_append_tokens_kernel(const QuantArgs a) {
     constexpr int EB = elem_bytes<IN>::value;
     constexpr uint32_t CW = BITS;  // bytes of packed codes per lane and row (8 channels)
@@ -41,7 +41,8 @@ __global__ void __launch_bounds__(kBlock) quantize_append_tokens_kernel(const Qu
     const char* src = static_cast<const char*>(kv ? a.v : a.k) + in_off * EB;
     const int64_t tile = (((int64_t)l * 2 + kv) * a.capacity_groups + t) * H + h;
     char* codes_t = reinterpret_cast<char*>(a.codes + tile * ((int64_t)G * d * BITS / 8));
-    f32x2* meta_t = reinterpret_cast<f32x2*>(a.meta) + tile * (int64_t)d;  // [d] (scale, zero)
+    typedef typename MetaPair<MB>::type meta_pair;  // two float32, or two bfloat16 in one word
+    meta_pair* meta_t = reinterpret_cast<meta_pair*>(a.meta) + tile * (int64_t)d;  // [d] (scale, zero)
     const uint32_t in_row_bytes = (uint32_t)a.stride_token * EB;
     const uint32_t in_lane = (uint32_t)row0 * in_row_bytes + (uint32_t)slot * 8u * EB;
     const uint32_t code_lane = ((uint32_t)row0 * lpr + slot) * CW;
@@ -114,15 +115,13 @@ __global__ void __launch_bounds__(kBlock) quantize_append_tokens_kernel(const Qu
         }
         cmn = cmn + 0.0f;  // never store -0 as a zero point
         float s = div_levels_exact<BITS>(__fsub_rn(cmx, cmn));
-        float inv;
-        if (s >= 1.17549435e-38f) {
-            inv = rcp_scale<BITS>(s);
-        } else {
-            s = 0.0f;
-            inv = 0.0f;
-        }
+        if (!(s >= 1.17549435e-38f)) s = 0.0f;
+        meta_pair stored;
+        if constexpr (MB) stored = round_pair_bf16(s, cmn);  // the codes follow the rounded pair
+        else stored = f32x2{s, cmn};
+        const float inv = s >= 1.17549435e-38f ? rcp_scale<BITS>(s) : 0.0f;
         const int c = (q % lpr) * 8 + q / lpr;
-        meta_t[c] = f32x2{s, cmn};
+        meta_t[c] = stored;
         fin[q] = f32x2{cmn, inv};
     }
     __syncthreads();
@@ -140,7 +139,10 @@ __global__ void __launch_bounds__(kBlock) quantize_append_tokens_kernel(const Qu
             float x[8], tq[8];
             widen(raw, x);
 #pragma unroll
-            for (int i = 0; i < 8; ++i) tq[i] = __builtin_fmaf(__fsub_rn(x[i], zm[i]), zi[i], 8388608.0f);
+            for (int i = 0; i < 8; ++i) {
+                tq[i] = __builtin_fmaf(__fsub_rn(x[i], zm[i]), zi[i], 8388608.0f);
+                if constexpr (MB) tq[i] = clamp_code<BITS>(tq[i]);  // m may lie above the minimum
+            }
             store_codes8<BITS>(codes_t + (code_lane + (uint32_t)rb * lpr * CW), tq);
         };
         if (HOLD > 0) {
@@ -185,22 +187,21 @@ __global__ void __launch_bounds__(kBlock) quantize_append_tokens_kernel(const Qu
     }
 }
 
-template <typename IN, int HOLD>
-hipError_t launch_h(const QuantArgs& a, hipStream_t s) {
+template <typename IN, int HOLD, int BITS, bool MB>
+hipError_t launch_m(const QuantArgs& a, hipStream_t s) {
     const dim3 grid(a.n_kv_heads, 2 * a.n_layers, a.n_frames);
     const size_t lds = (size_t)a.head_dim * sizeof(f32x2);
-    if (a.bits == 2) {
-        if (a.ksum != a.k)
-            quantize_append_tokens_kernel<IN, true, HOLD, 2><<<grid, dim3(kBlock), lds, s>>>(a);
-        else
-            quantize_append_tokens_kernel<IN, false, HOLD, 2><<<grid, dim3(kBlock), lds, s>>>(a);
-    } else {
-        if (a.ksum != a.k)
-            quantize_append_tokens_kernel<IN, true, HOLD, 4><<<grid, dim3(kBlock), lds, s>>>(a);
-        else
-            quantize_append_tokens_kernel<IN, false, HOLD, 4><<<grid, dim3(kBlock), lds, s>>>(a);
-    }
+    if (a.ksum != a.k)
+        quantize_append_tokens_kernel<IN, true, HOLD, BITS, MB><<<grid, dim3(kBlock), lds, s>>>(a);
+    else
+        quantize_append_tokens_kernel<IN, false, HOLD, BITS, MB><<<grid, dim3(kBlock), lds, s>>>(a);
     return hipGetLastError();
+}
+
+template <typename IN, int HOLD>
+hipError_t launch_h(const QuantArgs& a, hipStream_t s) {
+    if (a.meta_bf16) return a.bits == 2 ? launch_m<IN, HOLD, 2, true>(a, s) : launch_m<IN, HOLD, 4, true>(a, s);
+    return a.bits == 2 ? launch_m<IN, HOLD, 2, false>(a, s) : launch_m<IN, HOLD, 4, false>(a, s);
 }
 
 template <typename IN>

@@ -43,7 +43,7 @@ class TomError(RuntimeError):
 class tom_oqm_config_t(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "n_layers", "n_kv_heads", "n_q_heads", "head_dim", "group_tokens", "qgroup", "qaxis",
-        "bits", "capacity_groups", "in_dtype", "out_dtype", "sim")]
+        "bits", "capacity_groups", "in_dtype", "out_dtype", "sim", "meta_dtype")]
 
 
 class tom_oqm_sizes_t(C.Structure):
@@ -237,9 +237,9 @@ def tom_oqm_stream_probe(mode: int, src, dst, items: int, stream=None) -> None:
 # --------------------------------------------------------------------------- convenience
 def make_config(n_layers, n_kv_heads, n_q_heads, head_dim, group_tokens, qgroup, capacity_groups,
                 qaxis=TOM_QAXIS_HEAD_DIM, bits=4, in_dtype=TOM_BF16, out_dtype=TOM_BF16,
-                sim=TOM_SIM_COSINE) -> tom_oqm_config_t:
+                sim=TOM_SIM_COSINE, meta_dtype=TOM_F32) -> tom_oqm_config_t:
     return tom_oqm_config_t(n_layers, n_kv_heads, n_q_heads, head_dim, group_tokens, qgroup,
-                            qaxis, bits, capacity_groups, in_dtype, out_dtype, sim)
+                            qaxis, bits, capacity_groups, in_dtype, out_dtype, sim, meta_dtype)
 
 
 @dataclass
@@ -249,7 +249,7 @@ class Memory:
     cfg: tom_oqm_config_t
     handle: int
     codes: torch.Tensor
-    meta: torch.Tensor     # float32 (scale, zero) pairs
+    meta: torch.Tensor     # (scale, zero) pairs, float32 or bfloat16 (cfg.meta_dtype)
     keys: torch.Tensor
 
     @staticmethod
@@ -257,7 +257,10 @@ class Memory:
         sizes = tom_oqm_query_sizes(cfg)
         h = tom_oqm_create(cfg)
         codes = torch.empty(sizes.codes, dtype=torch.uint8, device=device)
-        meta = torch.empty(sizes.meta // 4, dtype=torch.float32, device=device)
+        if cfg.meta_dtype == TOM_BF16:
+            meta = torch.empty(sizes.meta // 2, dtype=torch.bfloat16, device=device)
+        else:
+            meta = torch.empty(sizes.meta // 4, dtype=torch.float32, device=device)
         keys = torch.empty(sizes.keys // 4, dtype=torch.float32, device=device)
         tom_oqm_bind(h, codes, meta, keys)
         return Memory(cfg, h, codes, meta, keys)

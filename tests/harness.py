@@ -17,23 +17,23 @@ def bits(t: torch.Tensor) -> np.ndarray:
 
 
 def make_pair(oqm, *, n_layers, n_kv_heads, n_q_heads, head_dim, group_tokens, qgroup, capacity,
-              in_dtype="bf16", out_dtype=None, sim="cosine", qaxis=0, bits=4):
+              in_dtype="bf16", out_dtype=None, sim="cosine", qaxis=0, bits=4, meta="f32"):
     out_dtype = out_dtype or in_dtype
     simc = 1 if sim == "cosine" else 0
     ocfg = orc.make_config(n_layers, n_kv_heads, n_q_heads, head_dim, group_tokens, qgroup,
                            capacity, qaxis=qaxis, bits=bits, in_dtype=DT[in_dtype][0],
-                           out_dtype=DT[out_dtype][0], sim=simc)
+                           out_dtype=DT[out_dtype][0], sim=simc, meta_dtype=DT[meta][0])
     gcfg = oqm.make_config(n_layers, n_kv_heads, n_q_heads, head_dim, group_tokens, qgroup,
                            capacity, qaxis=qaxis, bits=bits, in_dtype=DT[in_dtype][0],
-                           out_dtype=DT[out_dtype][0], sim=simc)
+                           out_dtype=DT[out_dtype][0], sim=simc, meta_dtype=DT[meta][0])
     return orc.new_store(ocfg), oqm.Memory.allocate(gcfg)
 
 
-def pair_for(oqm, w: synth_kv.Workload, capacity=None, out_dtype=None, qaxis=0, bits=4):
+def pair_for(oqm, w: synth_kv.Workload, capacity=None, out_dtype=None, qaxis=0, bits=4, meta="f32"):
     return make_pair(oqm, n_layers=w.n_layers, n_kv_heads=w.n_kv_heads, n_q_heads=w.n_q_heads,
                      head_dim=w.head_dim, group_tokens=w.group_tokens, qgroup=w.qgroup,
                      capacity=capacity or w.n_frames, in_dtype=w.dtype, out_dtype=out_dtype,
-                     sim=w.sim, qaxis=qaxis, bits=bits)
+                     sim=w.sim, qaxis=qaxis, bits=bits, meta=meta)
 
 
 def append_both(oqm, st, mem, k: torch.Tensor, v: torch.Tensor, ksum: torch.Tensor | None = None):
@@ -72,7 +72,10 @@ def compare_storage(st, mem, lo=0, hi=None):
     hi = st.n_groups if hi is None else hi
     assert mem.n_groups == st.n_groups
     oc, os_, oz, ok = storage_views(cfg, st.codes, st.scale, st.zero, st.keys)
-    meta = mem.meta.cpu().numpy().reshape(-1, 2)         # (scale, zero) pairs
+    if mem.meta.dtype == torch.bfloat16:                 # widen the stored bfloat16 pairs (exact)
+        meta = (bits(mem.meta).astype(np.uint32) << 16).view(np.float32).reshape(-1, 2)
+    else:
+        meta = mem.meta.cpu().numpy().reshape(-1, 2)     # (scale, zero) pairs
     gc, gs_, gz, gk = storage_views(cfg, mem.codes.cpu().numpy(), np.ascontiguousarray(meta[:, 0]),
                                     np.ascontiguousarray(meta[:, 1]), mem.keys.cpu().numpy())
     sl = slice(lo, hi)

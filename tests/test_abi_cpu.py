@@ -48,7 +48,8 @@ def test_sizes_follow_the_documented_layout(oqm):
     ("head_dim", 100, "INVALID"), ("qgroup", 48, "INVALID"), ("qgroup", 4, "UNSUPPORTED"),
     ("bits", 3, "INVALID"), ("bits", 8, "INVALID"), ("n_q_heads", 27, "INVALID"),
     ("group_tokens", 0, "INVALID"), ("capacity_groups", 0, "INVALID"), ("in_dtype", 7, "INVALID"),
-    ("sim", 2, "INVALID"), ("qaxis", 5, "INVALID")])
+    ("sim", 2, "INVALID"), ("qaxis", 5, "INVALID"), ("meta_dtype", 2, "UNSUPPORTED"),
+    ("meta_dtype", 9, "INVALID")])
 def test_bad_configurations_are_rejected(oqm, field, value, status):
     cfg = oqm.make_config(2, 4, 28, 128, 196, 64, 16)
     setattr(cfg, field, value)
@@ -151,6 +152,12 @@ def test_two_bit_sizes(oqm):
     s = oqm.tom_oqm_query_sizes(cfg)
     tiles = 28 * 2 * 100 * 4
     assert s.codes == tiles * 50 * 32 and s.meta == tiles * 50 * 2 * 2 * 4
+
+
+def test_bf16_metadata_sizes(oqm):
+    cfg = oqm.make_config(28, 4, 28, 128, 196, 64, 1024, meta_dtype=oqm.TOM_BF16)
+    s = oqm.tom_oqm_query_sizes(cfg)
+    assert s.meta == 28 * 2 * 1024 * 4 * 196 * 2 * 2 * 2      # half of the float32 pairs
 
 
 def test_token_axis_sizes(oqm):

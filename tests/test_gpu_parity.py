@@ -21,8 +21,8 @@ def oqm():
 
 
 def _stream_and_check(oqm, w, frames_per_call, k=None, path=None, want_tokens=False, out_dtype=None,
-                      qaxis=0, bits=4):
-    st, mem = H.pair_for(oqm, w, out_dtype=out_dtype, qaxis=qaxis, bits=bits)
+                      qaxis=0, bits=4, meta="f32"):
+    st, mem = H.pair_for(oqm, w, out_dtype=out_dtype, qaxis=qaxis, bits=bits, meta=meta)
     try:
         f = 0
         while f < w.n_frames:
@@ -119,6 +119,18 @@ def test_two_bit_extreme_ranges(oqm):
             H.compare_storage(st, mem)
         finally:
             mem.close()
+
+
+@pytest.mark.parametrize("qaxis,bits,G,d,gs,dt,H_k,H_q", [
+    (0, 4, 196, 128, 64, "bf16", 4, 28), (0, 4, 50, 128, 32, "f16", 4, 28), (1, 4, 50, 128, 64, "f16", 4, 28),
+    (1, 4, 196, 128, 64, "bf16", 4, 28), (0, 2, 196, 128, 64, "bf16", 4, 28), (1, 2, 50, 128, 64, "f16", 4, 28),
+    (0, 4, 13, 96, 8, "f32", 3, 6), (1, 4, 300, 64, 64, "f32", 2, 2), (0, 2, 33, 256, 128, "f32", 2, 4)])
+def test_bf16_metadata(oqm, qaxis, bits, G, d, gs, dt, H_k, H_q):
+    """(scale, zero) kept as bfloat16 pairs: rounded before the codes are taken, codes clamped;
+    codes, stored pairs, indices and reconstructed values bit-exact against the oracle."""
+    w = synth_kv.Workload("X", 2, H_k, H_q, d, G, 10, gs, 5, 4, dt, "cosine", 1300 + G + d + bits, "outlier", 10)
+    r = _stream_and_check(oqm, w, 4, qaxis=qaxis, bits=bits, meta="bf16")
+    assert r["k_eff"] == 4 and r["loose_rows"] == 0
 
 
 def test_mixed_in_out_dtypes(oqm):
@@ -425,10 +437,11 @@ def test_random_configurations_sweep(oqm):
         sim = str(rng.choice(["cosine", "dot"]))
         kind = str(rng.choice(["normal", "layer_std", "outlier"]))
         path = oqm.TOM_SCORE_TOKEN_GEMM if rng.integers(0, 2) else None
+        meta = str(rng.choice(["f32", "bf16"]))
         w = synth_kv.Workload("R", L, Hk, Hk * r, d, G, T, gs, tq, k, dt, sim, 9000 + case, kind, per_call)
-        print(f"case {case}: {w} qaxis={qaxis} bits={bits} path={path}", flush=True)
+        print(f"case {case}: {w} qaxis={qaxis} bits={bits} path={path} meta={meta}", flush=True)
         res = _stream_and_check(oqm, w, per_call, path=path, want_tokens=path is not None, qaxis=qaxis,
-                                bits=bits)
+                                bits=bits, meta=meta)
         assert res["k_eff"] == min(k, T)
 
 
