@@ -27,13 +27,13 @@ def oqm():
     return m
 
 
-def _oracle_sample(w, sampled_groups, fpa, qaxis=0, bits=4):
+def _oracle_sample(w, sampled_groups, fpa, qaxis=0, bits=4, meta_dtype=0):
     """Oracle store holding only the sampled frame-groups: slot j <-> group sampled_groups[j]."""
     orc = H.orc
     dt = H.DT[w.dtype][0]
     cfg = orc.make_config(w.n_layers, w.n_kv_heads, w.n_q_heads, w.head_dim, w.group_tokens,
                           w.qgroup, len(sampled_groups), qaxis=qaxis, bits=bits, in_dtype=dt, out_dtype=dt,
-                          sim=1 if w.sim == "cosine" else 0)
+                          sim=1 if w.sim == "cosine" else 0, meta_dtype=meta_dtype)
     st = orc.new_store(cfg)
     for t in sampled_groups:
         f0 = (t // fpa) * fpa
@@ -50,6 +50,8 @@ def _compare_sampled_storage(w, st, mem, sampled_groups):
     L, Hk, G, d, gs, T = w.n_layers, w.n_kv_heads, w.group_tokens, w.head_dim, w.qgroup, mem.cfg.capacity_groups
     codes = mem.codes.view(L, 2, T, Hk, G, d * cfg.bits // 8)
     meta = mem.meta.view(L, 2, T, Hk, G, d // gs, 2) if cfg.qaxis == 0 else mem.meta.view(L, 2, T, Hk, d, 2)
+    if meta.dtype == torch.bfloat16:
+        meta = meta.float()                                           # exact widening of the stored pairs
     keys = mem.keys.view(L, T, Hk, d)
     oc, os_, oz, ok = H.storage_views(cfg, st.codes, st.scale, st.zero, st.keys)
     not_identical = 0
@@ -144,16 +146,20 @@ def test_bulk_stream_full_size(oqm, name):
         mem.close()
 
 
-@pytest.mark.parametrize("G,dt,qaxis,bits", [(50, "f16", 1, 4),      # the paper's own setting (Eq. 9, 50 tokens, FP16)
-                                             (196, "bf16", 0, 2),    # 2-bit ablation at the benchmark's shape
-                                             (50, "f16", 1, 2)])
-def test_variants_full_size(oqm, G, dt, qaxis, bits):
+@pytest.mark.parametrize("G,dt,qaxis,bits,meta", [
+    (50, "f16", 1, 4, "f32"),       # the paper's own setting (Eq. 9, 50 tokens, FP16)
+    (196, "bf16", 0, 2, "f32"),     # 2-bit ablation at the benchmark's shape
+    (50, "f16", 1, 2, "f32"),
+    (196, "bf16", 0, 4, "bf16"),    # bfloat16 (scale, zero) pairs at the benchmark's shape
+    (50, "f16", 1, 4, "bf16")])
+def test_variants_full_size(oqm, G, dt, qaxis, bits, meta):
     """The 1024-frame, 28-layer stream with the token-axis quantizer and / or 2-bit codes."""
     w = synth_kv.scaled(synth_kv.WORKLOADS["C3"], group_tokens=G, dtype=dt)
     fpa = w.frames_per_append
     dtc = H.DT[dt][0]
     cfg = oqm.make_config(w.n_layers, w.n_kv_heads, w.n_q_heads, w.head_dim, G, w.qgroup, w.n_frames,
-                          qaxis=qaxis, bits=bits, in_dtype=dtc, out_dtype=dtc, sim=oqm.TOM_SIM_COSINE)
+                          qaxis=qaxis, bits=bits, in_dtype=dtc, out_dtype=dtc, sim=oqm.TOM_SIM_COSINE,
+                          meta_dtype=H.DT[meta][0])
     mem = oqm.Memory.allocate(cfg)
     try:
         for f0 in range(0, w.n_frames, fpa):
@@ -162,7 +168,7 @@ def test_variants_full_size(oqm, G, dt, qaxis, bits):
             torch.cuda.synchronize()
             del k, v
         sampled = [0, 31, 32, 500, 1000, w.n_frames - 1]
-        st = _oracle_sample(w, sampled, fpa, qaxis, bits)
+        st = _oracle_sample(w, sampled, fpa, qaxis, bits, H.DT[meta][0])
         assert _compare_sampled_storage(w, st, mem, sampled) <= 2
         _retrieve_and_check(oqm, w, st, mem, sampled, oqm.TOM_SCORE_MEAN_QUERY, synth_kv.query(w, 0, "cuda"),
                             w.n_frames)
