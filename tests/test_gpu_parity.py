@@ -445,6 +445,63 @@ def test_random_configurations_sweep(oqm):
         assert res["k_eff"] == min(k, T)
 
 
+def test_side_stream_and_graph_replay(oqm):
+    """The calls only queue work on the stream they are given: the path on a non-default
+    stream, and the one-call retrieval captured into a HIP graph and replayed several times
+    with eager work in between, must give what the eager default-stream calls give."""
+    w = synth_kv.Workload("X", 3, 4, 28, 128, 50, 40, 64, 8, 6, "bf16", "cosine", 4242, "layer_std", 40)
+    st, mem = H.pair_for(oqm, w)
+    try:
+        L, Hk, G, d, k, T = w.n_layers, w.n_kv_heads, w.group_tokens, w.head_dim, w.top_k, w.n_frames
+        kk, vv = synth_kv.kv_frames(w, 0, T)
+        H.orc.quantize_append(st, H.bits(kk), H.bits(vv))
+        side = torch.cuda.Stream()                               # default priority
+        kd, vd = kk.cuda(), vv.cuda()
+        qs = [synth_kv.query(w, i).cuda() for i in range(3)]
+        scores = torch.empty((L, T), dtype=torch.float32, device="cuda")
+        idx = torch.full((L, k), -7, dtype=torch.int32, device="cuda")
+        ko = torch.zeros((L, Hk, k * G, d), dtype=torch.bfloat16, device="cuda")
+        vo = torch.zeros_like(ko)
+        ws = torch.empty(oqm.tom_oqm_score_workspace_bytes(mem.handle, L, w.t_q, oqm.TOM_SCORE_AUTO),
+                         dtype=torch.uint8, device="cuda")
+        qbuf = qs[0].clone()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            oqm.tom_oqm_quantize_append(mem.handle, 0, L, T, kd, vd, stream=side.cuda_stream)
+            oqm.tom_oqm_retrieve(mem.handle, 0, L, qbuf, w.t_q, k, scores, T, idx, ko, vo, ws,
+                                 stream=side.cuda_stream)
+        side.synchronize()
+        H.compare_storage(st, mem)
+
+        def reference(q):
+            sc = H.orc.score_groups(st, H.bits(q), 1)
+            ii, k_eff = H.orc.topk(sc, k)
+            rk, rv = H.orc.dequant_gather(st, ii, k_eff)
+            return ii, rk, rv
+
+        ii, rk, rv = reference(qs[0])
+        assert np.array_equal(idx.cpu().numpy(), ii) and np.array_equal(H.bits(ko), rk) and np.array_equal(H.bits(vo), rv)
+
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            oqm.tom_oqm_retrieve(mem.handle, 0, L, qbuf, w.t_q, k, scores, T, idx, ko, vo, ws,
+                                 stream=torch.cuda.current_stream().cuda_stream)
+        for rep in range(4):
+            q = qs[rep % 3]
+            qbuf.copy_(q)                                        # eager work between the replays
+            ko.zero_()
+            vo.zero_()
+            idx.fill_(-7)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            ii, rk, rv = reference(q)
+            assert np.array_equal(idx.cpu().numpy(), ii), f"replay {rep}"
+            assert np.array_equal(H.bits(ko), rk) and np.array_equal(H.bits(vo), rv), f"replay {rep}"
+    finally:
+        mem.close()
+
+
 def test_division_shortcuts_are_exact_for_every_input():
     """The quantize kernel computes (max - min) / 15 and 1 / s with one FMA correction step
     instead of the full IEEE division sequence; the library's self-check program compares
