@@ -198,6 +198,40 @@ def test_quantize_invariants(oracle):
     assert np.all(np.abs(x - xh) <= bound)
 
 
+@pytest.mark.parametrize("seed", range(6))
+@pytest.mark.parametrize("qaxis,bits,meta", [(0, 4, 0), (0, 2, 0), (1, 4, 0), (1, 2, 0), (0, 4, 1), (1, 2, 1)])
+def test_quantizer_properties_on_random_tiles(oracle, seed, qaxis, bits, meta):
+    """Every variant, random shapes and value recipes: codes in range, monotone inside a
+    quant-group, extremes at the ends (float32 metadata), reconstruction within the bound."""
+    r = _rng(1000 * seed + 7 * qaxis + bits + 100 * meta)
+    G = int(r.choice([1, 2, 7, 16, 50, 61]))
+    d = int(r.choice([8, 32, 64, 128]))
+    gs = int(r.choice([g for g in (8, 16, 32, 64, 128) if d % g == 0]))
+    kind = int(r.integers(0, 3))
+    x = r.standard_normal((G, d)) if kind == 0 else r.standard_t(3, (G, d)) * 3 if kind == 1 else \
+        r.standard_normal((G, d)) * np.exp(r.uniform(-8, 8, (1, d)))
+    x = (x + r.uniform(-4, 4)).astype(np.float32)
+    levels = (1 << bits) - 1
+    codes, packed, scale, zero = oracle.quantize_tile(x, gs, qaxis, bits, meta)
+    assert codes.max() <= levels
+    if qaxis == 0:
+        xg, cg = x.reshape(G, d // gs, gs), codes.reshape(G, d // gs, gs)
+        step, zpt = np.repeat(scale, gs, axis=1), np.repeat(zero, gs, axis=1)
+    else:
+        xg, cg = x.T, codes.T                                      # [d][G]: a group per channel
+        step, zpt = np.broadcast_to(scale, (G, d)), np.broadcast_to(zero, (G, d))
+    order = np.argsort(xg, -1, kind="stable")
+    assert np.all(np.diff(np.take_along_axis(cg.astype(np.int32), order, -1), axis=-1) >= 0)
+    live = (xg.max(-1) - xg.min(-1)) / levels >= np.finfo(np.float32).tiny
+    if meta == 0:
+        assert np.array_equal(zero.reshape(xg.shape[:-1]), xg.min(-1) + np.float32(0))
+        assert np.all(np.take_along_axis(cg, xg.argmin(-1)[..., None], -1) == 0)
+        assert np.all(np.take_along_axis(cg, xg.argmax(-1)[..., None], -1)[live] == levels)
+    xh = oracle.dequant_tile(packed, scale, zero, G, d, gs, qaxis, bits)
+    slack = 2.0 ** -8 if meta else 2.0 ** -22
+    assert np.all(np.abs(x - xh) <= 0.5 * step * (1 + 1e-5) + slack * (np.abs(zpt) + levels * step) + 1e-30)
+
+
 def test_grid_points_round_trip_exactly(oracle):
     # inputs m + c*s with dyadic s reproduce c and dequantize exactly
     G, d, gs = 4, 64, 32
