@@ -228,6 +228,7 @@ static tom_status_t score_impl(const tom_oqm_t* h, int32_t layer0, int32_t n_lay
     if (score_stride < T) return fail(TOM_ERR_INVALID_ARG, "score_stride %lld < stored groups %d",
                                       (long long)score_stride, T);
     if (T == 0 || n_layers == 0) return TOM_OK;
+    if (n_layers > 65535) return fail(TOM_ERR_UNSUPPORTED, "at most 65535 layers per call");
     if (!q || !scores) return fail(TOM_ERR_INVALID_ARG, "q and scores must be non-NULL");
     if (!aligned16(q)) return fail(TOM_ERR_INVALID_ARG, "q must be 16-byte aligned");
     const int rpath = resolve_path(path, token_scores != nullptr);
