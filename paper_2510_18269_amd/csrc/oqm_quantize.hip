@@ -25,9 +25,18 @@
 namespace oqm {
 namespace {
 
-constexpr int kUnroll = 2;  // token rows per lane and loop trip
+// Token rows per lane and loop trip.  Two keep the register footprint small, which is what a
+// launch of many tiles wants (more resident workgroups).  A launch with at most one tile per
+// compute unit (one frame of a live stream: 224 tiles at 28 layers x 4 heads) is bound by the
+// dependent memory round trips of that one workgroup instead, so it takes all rows of a lane
+// at once (13 at 196 x 128: one trip).  Measured kernel time at 224 tiles: 8.3 against 9.8 us;
+// from two tiles per compute unit on, the two-row form is the faster one (11.3 against 11.8 us
+// at 448 tiles, 15.9 against 18.5 us at 896).
+constexpr int kUnrollStream = 2;
+constexpr int kUnrollShallow = 13;
+constexpr int64_t kShallowTiles = 256;  // compute units of the chip
 
-template <typename IN, int LPG, bool SEPARATE_SUMMARY, int BITS, bool MB>
+template <typename IN, int LPG, bool SEPARATE_SUMMARY, int BITS, bool MB, int kUnroll>
 __global__ void __launch_bounds__(kBlock) quantize_append_kernel(const QuantArgs a) {
     constexpr int EB = elem_bytes<IN>::value;
     constexpr uint32_t CW = BITS;  // bytes of packed codes per lane and row (8 channels)
@@ -162,10 +171,13 @@ __global__ void __launch_bounds__(kBlock) quantize_append_kernel(const QuantArgs
 template <typename IN, int LPG, int BITS, bool MB>
 hipError_t launch_b(const QuantArgs& a, hipStream_t s) {
     const dim3 grid(a.n_kv_heads, 2 * a.n_layers, a.n_frames);
+    const bool shallow = (int64_t)grid.x * grid.y * grid.z <= kShallowTiles;
     if (a.ksum != a.k)
-        quantize_append_kernel<IN, LPG, true, BITS, MB><<<grid, dim3(kBlock), 0, s>>>(a);
+        quantize_append_kernel<IN, LPG, true, BITS, MB, kUnrollStream><<<grid, dim3(kBlock), 0, s>>>(a);
+    else if (shallow)
+        quantize_append_kernel<IN, LPG, false, BITS, MB, kUnrollShallow><<<grid, dim3(kBlock), 0, s>>>(a);
     else
-        quantize_append_kernel<IN, LPG, false, BITS, MB><<<grid, dim3(kBlock), 0, s>>>(a);
+        quantize_append_kernel<IN, LPG, false, BITS, MB, kUnrollStream><<<grid, dim3(kBlock), 0, s>>>(a);
     return hipGetLastError();
 }
 

@@ -133,6 +133,23 @@ def test_bf16_metadata(oqm, qaxis, bits, G, d, gs, dt, H_k, H_q):
     assert r["k_eff"] == 4 and r["loose_rows"] == 0
 
 
+@pytest.mark.parametrize("bits,meta,dt,G,d,gs,H_k,frames", [
+    (4, "f32", "bf16", 50, 128, 64, 4, 20), (2, "f32", "f16", 13, 96, 8, 3, 24),
+    (4, "bf16", "f32", 33, 256, 128, 2, 40), (2, "bf16", "bf16", 196, 128, 64, 4, 17)])
+def test_append_launches_above_and_below_one_tile_per_cu(oqm, bits, meta, dt, G, d, gs, H_k, frames):
+    """The head_dim-axis append has two forms of one kernel: all rows of a lane in flight for
+    launches of at most 256 tiles, two rows per trip above.  Most cases in this file are small
+    launches; here one call stores more than 256 tiles, then the same stream goes in frame by
+    frame, and both must match the oracle."""
+    w = synth_kv.Workload("X", 2, H_k, 2 * H_k, d, G, frames, gs, 5, 6, dt, "cosine", 2100 + G + d + bits,
+                          "layer_std", frames)
+    assert H_k * 2 * 2 * frames > 256
+    r = _stream_and_check(oqm, w, frames, bits=bits, meta=meta)
+    assert r["k_eff"] == 6 and r["loose_rows"] == 0
+    r = _stream_and_check(oqm, w, 1, bits=bits, meta=meta)
+    assert r["k_eff"] == 6 and r["loose_rows"] == 0
+
+
 def test_mixed_in_out_dtypes(oqm):
     w = synth_kv.scaled(synth_kv.WORKLOADS["C2"], n_frames=9, top_k=3)
     for out in ("f32", "f16", "bf16"):
