@@ -201,3 +201,14 @@ def test_topk_argument_checks_and_k_eff(oqm):
 def test_k_from_budget_matches_the_supplement_formula(oqm, oracle):
     for B, G, T in [(12544, 196, 1000), (12544, 50, 10 ** 6), (12544, 50, 7), (1, 50, 10), (0, 50, 10)]:
         assert oqm.tom_oqm_k_from_budget(B, G, T) == oracle.k_from_budget(B, G, T * G)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The path has no collectives: `bench.py --gpus N` with N > 1 exits with a message and
+    touches no GPU (the check comes before torch is imported)."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=60)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
