@@ -24,12 +24,18 @@ COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=
           "-Wall", "-Wno-unused-result", "-I", INCLUDE, "-I", CSRC]
 
 
+# Per-file additions.  The score contraction keeps its float64 accumulators in ordinary vector
+# registers: without this the compiler moves all 32 of them to the accumulation file and back
+# around every staged chunk (64 copies per 32 MFMAs).
+EXTRA = {"oqm_score.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
+
+
 def build(verbose: bool = False) -> str:
     os.makedirs(OBJ, exist_ok=True)
 
     def compile_one(src: str) -> str:
         obj = os.path.join(OBJ, src.replace(".hip", ".o"))
-        cmd = ["hipcc", *COMMON, "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = ["hipcc", *COMMON, *EXTRA.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         r = subprocess.run(cmd, capture_output=True, text=True)

@@ -214,8 +214,12 @@ constexpr int kGemmM = 64;
 #define OQM_GEMM_K 32
 #endif
 constexpr int kGemmK = OQM_GEMM_K;
-constexpr int kLdA = kGemmK + 4;  // doubles; 2-way LDS bank conflict at most (the minimum for b64)
-constexpr int kLdB = kGemmK + 4;  // floats; conflict-free fragment reads
+// Row pitches of the staged operands.  A fragment read takes element (row fi, column kk) per
+// lane: with 34 doubles per row the 32 lanes of a half-wave fall on 4*fi + 2*kk, i.e. on all
+// 32 even banks once (a pitch of 36 puts rows fi and fi + 8 on the same banks: measured 9 %
+// slower); with 36 floats per row the 64 lanes of a B read fall on 64 different banks.
+constexpr int kLdA = kGemmK + 2;  // doubles
+constexpr int kLdB = kGemmK + 4;  // floats
 
 __device__ __forceinline__ int mfma_d_row(int lane, int v) { return 4 * v + (lane >> 4); }
 
@@ -223,7 +227,7 @@ __device__ __forceinline__ int mfma_d_row(int lane, int v) { return 4 * v + (lan
 // of this wave.  No branches inside, so the LDS reads of a step are issued together.
 template <int MT>
 __device__ __forceinline__ void mma_chunk(const double* __restrict__ As, const float* __restrict__ Bs,
-                                          f64x4 (&acc)[kGemmM / 16], double& nk2c, int wave, int fi,
+                                          f64x4 (&acc)[MT], double& nk2c, int wave, int fi,
                                           int kk) {
 #pragma unroll
     for (int ks = 0; ks < kGemmK / 4; ++ks) {
@@ -238,6 +242,93 @@ __device__ __forceinline__ void mma_chunk(const double* __restrict__ As, const f
     }
 }
 
+// One block of up to 64 query rows: the chunk loop with the row-tile count fixed at compile
+// time, so the accumulators stay in place across the whole contraction.
+template <int MT>
+__device__ __forceinline__ void gemm_rows(const ScoreArgs& a, double (&As)[2][kGemmM * kLdA], float (&Bs)[2][kGemmN * kLdB],
+                                          const double* qtok, const float* keys, int m0, int n0, int li,
+                                          double& colsum, double& nk2) {
+    const int HD = a.n_kv_heads * a.head_dim;
+    const int T = a.n_groups, Tq = a.t_q;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int fi = lane & 15, kk = lane >> 4;
+    const int n_chunks = (HD + kGemmK - 1) / kGemmK;
+    constexpr int kALanes = kGemmK / 2, kBLanes = kGemmK / 4;
+    constexpr int kAPass = kBlock / kALanes, kBPass = kBlock / kBLanes;
+    constexpr int kARows = (MT * 16 + kAPass - 1) / kAPass, kBRows = kGemmN / kBPass;
+    const int a_row = tid / kALanes, a_col = (tid % kALanes) * 2;
+    const int b_row = tid / kBLanes, b_col = (tid % kBLanes) * 4;
+    const int rows = min(kGemmM, Tq - m0);
+
+    f64x4 acc[MT];
+#pragma unroll
+    for (int m = 0; m < MT; ++m) acc[m] = f64x4{0.0, 0.0, 0.0, 0.0};
+    double nk2c = 0.0;
+    double ra[kARows][2];
+    f32x4 rb[kBRows];
+    auto load_chunk = [&](int c) {
+        const int k0 = c * kGemmK;
+#pragma unroll
+        for (int i = 0; i < kARows; ++i) {
+            const int rr = a_row + i * kAPass;
+            ra[i][0] = 0.0;
+            ra[i][1] = 0.0;
+            if (rr < rows && k0 + a_col < HD) {
+                const double* p = qtok + (int64_t)(m0 + rr) * HD + k0 + a_col;
+                ra[i][0] = p[0];
+                ra[i][1] = p[1];
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < kBRows; ++i) {
+            const int rr = b_row + i * kBPass;
+            rb[i] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+            if (n0 + rr < T && k0 + b_col < HD)
+                rb[i] = *reinterpret_cast<const f32x4*>(keys + (int64_t)(n0 + rr) * HD + k0 + b_col);
+        }
+    };
+    auto store_chunk = [&](int stage) {
+#pragma unroll
+        for (int i = 0; i < kARows; ++i) {
+            const int rr = a_row + i * kAPass;
+            if (rr < MT * 16) {
+                As[stage][rr * kLdA + a_col] = ra[i][0];
+                As[stage][rr * kLdA + a_col + 1] = ra[i][1];
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < kBRows; ++i) {
+            const int rr = b_row + i * kBPass;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) Bs[stage][rr * kLdB + b_col + j] = rb[i][j];
+        }
+    };
+
+    __syncthreads();  // the previous row block no longer reads LDS
+    load_chunk(0);
+    store_chunk(0);
+    __syncthreads();
+    for (int c = 0; c < n_chunks; ++c) {
+        const int stage = c & 1;
+        if (c + 1 < n_chunks) load_chunk(c + 1);  // in flight during the MFMAs below
+        mma_chunk<MT>(As[stage], Bs[stage], acc, nk2c, wave, fi, kk);
+        if (c + 1 < n_chunks) store_chunk(stage ^ 1);  // that stage was consumed before the last barrier
+        __syncthreads();
+    }
+    if (m0 == 0) nk2 = nk2c;
+    const int t = n0 + wave * 16 + fi;
+#pragma unroll
+    for (int m = 0; m < MT; ++m) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int j = m0 + m * 16 + mfma_d_row(lane, v);
+            colsum += acc[m][v];  // rows >= T_q were staged as zeros
+            if (a.token_scores && j < Tq && t < T)
+                a.token_scores[((int64_t)li * Tq + j) * T + t] = (float)acc[m][v];
+        }
+    }
+}
+
 __global__ void __launch_bounds__(kBlock) score_token_gemm_kernel(const ScoreArgs a) {
     // two LDS stages: chunk c is multiplied while chunk c+1 travels global -> registers -> LDS
     __shared__ double As[2][kGemmM * kLdA];
@@ -246,96 +337,19 @@ __global__ void __launch_bounds__(kBlock) score_token_gemm_kernel(const ScoreArg
     const int n0 = blockIdx.x * kGemmN;
     const int HD = a.n_kv_heads * a.head_dim;
     const int T = a.n_groups, Tq = a.t_q;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int fi = lane & 15, kk = lane >> 4;
     const float* keys = a.keys + ((int64_t)(a.layer0 + li) * a.capacity_groups) * HD;
     const double* qtok = a.ws_qtok + (int64_t)li * Tq * HD;
-    const int n_chunks = (HD + kGemmK - 1) / kGemmK;
-
-    // staging roles: A = 64 token rows x kGemmK doubles, 16 B per lane; B = 64 groups x kGemmK
-    // floats, 16 B per lane
-    constexpr int kALanes = kGemmK / 2, kBLanes = kGemmK / 4;  // lanes per staged row
-    constexpr int kAPass = kBlock / kALanes, kBPass = kBlock / kBLanes;  // rows per pass
-    constexpr int kARows = kGemmM / kAPass, kBRows = kGemmN / kBPass;    // rows per thread
-    const int a_row = tid / kALanes, a_col = (tid % kALanes) * 2;
-    const int b_row = tid / kBLanes, b_col = (tid % kBLanes) * 4;
 
     double colsum = 0.0, nk2 = 0.0;
     for (int m0 = 0; m0 < Tq; m0 += kGemmM) {
-        const int rows = min(kGemmM, Tq - m0);
-        const int mt = (rows + 15) >> 4;
-        f64x4 acc[kGemmM / 16];
-#pragma unroll
-        for (int m = 0; m < kGemmM / 16; ++m) acc[m] = f64x4{0.0, 0.0, 0.0, 0.0};
-        double nk2c = 0.0;  // |key|^2 share of this lane, recomputed per row block
-
-        double ra[kARows][2];
-        f32x4 rb[kBRows];
-        auto load_chunk = [&](int c) {
-            const int k0 = c * kGemmK;
-#pragma unroll
-            for (int i = 0; i < kARows; ++i) {
-                const int rr = a_row + i * kAPass;
-                ra[i][0] = 0.0;
-                ra[i][1] = 0.0;
-                if (rr < rows && k0 + a_col < HD) {
-                    const double* p = qtok + (int64_t)(m0 + rr) * HD + k0 + a_col;
-                    ra[i][0] = p[0];
-                    ra[i][1] = p[1];
-                }
-            }
-#pragma unroll
-            for (int i = 0; i < kBRows; ++i) {
-                const int rr = b_row + i * kBPass;
-                rb[i] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-                if (n0 + rr < T && k0 + b_col < HD)
-                    rb[i] = *reinterpret_cast<const f32x4*>(keys + (int64_t)(n0 + rr) * HD + k0 + b_col);
-            }
-        };
-        auto store_chunk = [&](int stage) {
-#pragma unroll
-            for (int i = 0; i < kARows; ++i) {
-                const int rr = a_row + i * kAPass;
-                As[stage][rr * kLdA + a_col] = ra[i][0];
-                As[stage][rr * kLdA + a_col + 1] = ra[i][1];
-            }
-#pragma unroll
-            for (int i = 0; i < kBRows; ++i) {
-                const int rr = b_row + i * kBPass;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) Bs[stage][rr * kLdB + b_col + j] = rb[i][j];
-            }
-        };
-
-        __syncthreads();  // the previous row block no longer reads LDS
-        load_chunk(0);
-        store_chunk(0);
-        __syncthreads();
-        for (int c = 0; c < n_chunks; ++c) {
-            const int stage = c & 1;
-            if (c + 1 < n_chunks) load_chunk(c + 1);  // in flight during the MFMAs below
-            switch (mt) {  // uniform; straight-line MFMA code per row-tile count
-                case 1: mma_chunk<1>(As[stage], Bs[stage], acc, nk2c, wave, fi, kk); break;
-                case 2: mma_chunk<2>(As[stage], Bs[stage], acc, nk2c, wave, fi, kk); break;
-                case 3: mma_chunk<3>(As[stage], Bs[stage], acc, nk2c, wave, fi, kk); break;
-                default: mma_chunk<4>(As[stage], Bs[stage], acc, nk2c, wave, fi, kk); break;
-            }
-            if (c + 1 < n_chunks) store_chunk(stage ^ 1);  // that stage was consumed before the last barrier
-            __syncthreads();
-        }
-        if (m0 == 0) nk2 = nk2c;
-        const int t = n0 + wave * 16 + fi;
-#pragma unroll
-        for (int m = 0; m < kGemmM / 16; ++m) {
-            if (m < mt) {
-#pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const int j = m0 + m * 16 + mfma_d_row(lane, v);
-                    colsum += acc[m][v];  // rows >= T_q were staged as zeros
-                    if (a.token_scores && j < Tq && t < T)
-                        a.token_scores[((int64_t)li * Tq + j) * T + t] = (float)acc[m][v];
-                }
-            }
+        const int mt = (min(kGemmM, Tq - m0) + 15) >> 4;
+        switch (mt) {  // uniform
+            case 1: gemm_rows<1>(a, As, Bs, qtok, keys, m0, n0, li, colsum, nk2); break;
+            case 2: gemm_rows<2>(a, As, Bs, qtok, keys, m0, n0, li, colsum, nk2); break;
+            case 3: gemm_rows<3>(a, As, Bs, qtok, keys, m0, n0, li, colsum, nk2); break;
+            default: gemm_rows<4>(a, As, Bs, qtok, keys, m0, n0, li, colsum, nk2); break;
         }
     }
     // lanes fi, 16 + fi, 32 + fi, 48 + fi hold the partial sums of group n0 + 16*wave + fi
