@@ -129,8 +129,8 @@ def cpu_baseline(w, batches_cpu, q_cpu, threads, qaxis=0, bits=4, meta="f32"):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=40)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="C3", choices=["C2", "C3", "C4", "C5"])
     ap.add_argument("--frames-per-append", type=int, default=0, help="override the workload's batch")
     ap.add_argument("--qaxis", default="head_dim", choices=["head_dim", "tokens"],
@@ -267,7 +267,7 @@ def main():
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
-    EVENT_EVERY = 4
+    EVENT_EVERY = 8
     events = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] if i % EVENT_EVERY == 0 else None
               for i in range(args.steps)]
     t0 = time.perf_counter()
