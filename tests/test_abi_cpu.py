@@ -212,3 +212,20 @@ def test_bench_refuses_more_than_one_gpu():
                        capture_output=True, text=True, timeout=60)
     assert r.returncode != 0
     assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_product_and_oracle_do_not_reference_each_other():
+    """The library and its binding never touch the oracle (there is no CPU fallback), and the
+    oracle never touches the library: only the seeded input generator is common to both."""
+    pkg = os.path.join(ROOT, "paper_2510_18269_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower(), f"{f} mentions the oracle"
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith((".py", ".c", ".h")):
+            text = open(os.path.join(ROOT, "oracle", f)).read()
+            assert "paper_2510_18269_amd" not in text and "libtom_oqm" not in text and "tom_oqm.h" not in text, f
+    header = open(os.path.join(ROOT, "include", "tom_oqm.h")).read()
+    assert "tomref" not in header
