@@ -150,6 +150,21 @@ def test_append_launches_above_and_below_one_tile_per_cu(oqm, bits, meta, dt, G,
     assert r["k_eff"] == 6 and r["loose_rows"] == 0
 
 
+@pytest.mark.parametrize("qaxis,bits,d,gs,dt", [(0, 4, 2048, 128, "bf16"), (1, 4, 2048, 64, "f16"),
+                                               (0, 2, 1032, 8, "f32"), (1, 2, 1032, 8, "bf16"),
+                                               (0, 4, 1032, 8, "f16")])
+def test_widest_and_odd_head_dims(oqm, qaxis, bits, d, gs, dt):
+    """The widest head the configuration check admits (2048: one token row fills the whole
+    workgroup) and a width whose lane count per row (129) is neither a power of two nor a
+    divisor of the workgroup: every kernel of the path on both axes."""
+    w = synth_kv.Workload("X", 2, 2, 4, d, 5, 7, gs, 3, 3, dt, "cosine", 3100 + d + bits, "layer_std", 7)
+    r = _stream_and_check(oqm, w, 3, qaxis=qaxis, bits=bits)
+    assert r["k_eff"] == 3 and r["loose_rows"] == 0
+    r = _stream_and_check(oqm, synth_kv.scaled(w, t_q=18), 7, k=4, path=oqm.TOM_SCORE_TOKEN_GEMM,
+                          want_tokens=True, qaxis=qaxis, bits=bits)
+    assert r["k_eff"] == 4
+
+
 def test_mixed_in_out_dtypes(oqm):
     w = synth_kv.scaled(synth_kv.WORKLOADS["C2"], n_frames=9, top_k=3)
     for out in ("f32", "f16", "bf16"):
