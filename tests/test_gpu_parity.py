@@ -165,6 +165,16 @@ def test_widest_and_odd_head_dims(oqm, qaxis, bits, d, gs, dt):
     assert r["k_eff"] == 4
 
 
+@pytest.mark.parametrize("H_k,d", [(16, 512), (4, 2048)])
+def test_widest_flattened_key(oqm, H_k, d):
+    """H_k * d = 8192, the most the score kernels admit (64 KB of staged query per workgroup)."""
+    w = synth_kv.Workload("X", 1, H_k, 2 * H_k, d, 3, 6, 64, 2, 3, "bf16", "cosine", 3300 + d, "layer_std", 6)
+    r = _stream_and_check(oqm, w, 6)
+    assert r["k_eff"] == 3 and r["loose_rows"] == 0
+    r = _stream_and_check(oqm, synth_kv.scaled(w, t_q=5), 6, k=2, path=oqm.TOM_SCORE_TOKEN_GEMM, want_tokens=True)
+    assert r["k_eff"] == 2
+
+
 def test_mixed_in_out_dtypes(oqm):
     w = synth_kv.scaled(synth_kv.WORKLOADS["C2"], n_frames=9, top_k=3)
     for out in ("f32", "f16", "bf16"):
