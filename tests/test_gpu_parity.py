@@ -65,7 +65,8 @@ def test_reduced_multi_layer_streams(oqm, name, layers, frames, per_call):
 @pytest.mark.parametrize("G,d,gs,dt,H_k,H_q", [
     (50, 128, 64, "f16", 4, 28),      # the paper's 50-token groups, FP16 K/V
     (1, 64, 8, "f32", 1, 1), (197, 128, 128, "bf16", 2, 4), (13, 96, 32, "bf16", 3, 6),
-    (64, 256, 16, "f16", 2, 2), (33, 8, 8, "f32", 5, 5), (7, 512, 64, "bf16", 1, 3)])
+    (64, 256, 16, "f16", 2, 2), (33, 8, 8, "f32", 5, 5), (7, 512, 64, "bf16", 1, 3),
+    (500, 128, 64, "bf16", 2, 4)])    # 32 row passes per tile: every kernel's multi-trip loop
 def test_shapes_dtypes_and_ragged_tails(oqm, G, d, gs, dt, H_k, H_q):
     w = synth_kv.Workload("X", 2, H_k, H_q, d, G, 11, gs, 5, 4, dt, "cosine", 100 + G + d, "layer_std", 11)
     r = _stream_and_check(oqm, w, 4)
@@ -78,7 +79,8 @@ def test_shapes_dtypes_and_ragged_tails(oqm, G, d, gs, dt, H_k, H_q):
 @pytest.mark.parametrize("G,d,dt,H_k,H_q", [
     (50, 128, "f16", 4, 28),           # the paper's setting: 50-token groups, FP16, per-channel scale
     (196, 128, "bf16", 4, 28), (1, 64, "f32", 1, 1), (13, 96, "bf16", 3, 6), (300, 64, "f16", 2, 2),
-    (33, 8, "f32", 5, 5), (40, 512, "bf16", 1, 3)])
+    (33, 8, "f32", 5, 5), (40, 512, "bf16", 1, 3),
+    (500, 128, "bf16", 2, 4), (150, 128, "f32", 1, 2)])   # more rows per lane than the kernel keeps in registers
 def test_token_axis_quantizer(oqm, G, d, dt, H_k, H_q):
     """Eq. 9 as printed: scale and zero per head and channel over the G tokens of a group."""
     w = synth_kv.Workload("X", 2, H_k, H_q, d, G, 9, 64, 5, 4, dt, "cosine", 300 + G + d, "outlier", 9)
@@ -89,7 +91,8 @@ def test_token_axis_quantizer(oqm, G, d, dt, H_k, H_q):
 @pytest.mark.parametrize("qaxis,G,d,gs,dt,H_k,H_q", [
     (0, 196, 128, 64, "bf16", 4, 28), (0, 50, 128, 32, "f16", 4, 28), (1, 50, 128, 64, "f16", 4, 28),
     (1, 196, 128, 64, "bf16", 4, 28), (0, 13, 96, 8, "f32", 3, 6), (1, 300, 64, 64, "bf16", 2, 2),
-    (0, 1, 8, 8, "f32", 1, 1), (0, 33, 256, 128, "bf16", 2, 4)])
+    (0, 1, 8, 8, "f32", 1, 1), (0, 33, 256, 128, "bf16", 2, 4), (1, 500, 128, 64, "f16", 2, 2),
+    (0, 500, 128, 32, "bf16", 2, 2)])
 def test_two_bit_codes(oqm, qaxis, G, d, gs, dt, H_k, H_q):
     """The paper's bit-width ablation: 2-bit codes (three steps between min and max), four per
     byte, on both quantization axes."""
