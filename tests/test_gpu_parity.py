@@ -184,18 +184,25 @@ def test_mixed_in_out_dtypes(oqm):
         _stream_and_check(oqm, w, 9, out_dtype=out)
 
 
-def test_strided_input_layer_ranges_and_separate_summary(oqm):
+@pytest.mark.parametrize("qaxis,bits,meta,dt,G", [(0, 4, "f32", "bf16", 21), (1, 4, "f32", "f16", 21),
+                                                  (0, 2, "bf16", "f32", 21), (1, 2, "bf16", "bf16", 21),
+                                                  (1, 4, "f32", "bf16", 200), (1, 4, "f32", "f32", 300)])
+def test_strided_input_layer_ranges_and_separate_summary(oqm, qaxis, bits, meta, dt, G):
     """Token-major source buffers [F][G][L][H][d], layers appended one at a time with
-    commit only on the last, summary keys from a separate (pre-rotary) tensor."""
-    st, mem = H.make_pair(oqm, n_layers=3, n_kv_heads=2, n_q_heads=4, head_dim=64, group_tokens=21,
-                          qgroup=32, capacity=6, in_dtype="bf16")
+    commit only on the last, summary keys from a separate (pre-rotary) tensor; on both axes,
+    both code widths and metadata kinds (the token-axis cases with 200 and 300 tokens take the
+    forms that keep 8 rows per lane in registers and none at all: 7 and 10 row passes at d = 64)."""
+    tdt = {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}[dt]
+    eb = 4 if dt == "f32" else 2
+    st, mem = H.make_pair(oqm, n_layers=3, n_kv_heads=2, n_q_heads=4, head_dim=64, group_tokens=G,
+                          qgroup=32, capacity=6, in_dtype=dt, qaxis=qaxis, bits=bits, meta=meta)
     try:
         g = torch.Generator().manual_seed(9)
-        F, G, L, Hk, d = 2, 21, 3, 2, 64
+        F, L, Hk, d = 2, 3, 2, 64
         for call in range(2):
-            bk = torch.randn(F, G, L, Hk, d, generator=g).to(torch.bfloat16)
-            bv = torch.randn(F, G, L, Hk, d, generator=g).to(torch.bfloat16)
-            pre = torch.randn(F, G, L, Hk, d, generator=g).to(torch.bfloat16)
+            bk = torch.randn(F, G, L, Hk, d, generator=g).to(tdt)
+            bv = torch.randn(F, G, L, Hk, d, generator=g).to(tdt)
+            pre = torch.randn(F, G, L, Hk, d, generator=g).to(tdt)
             strides = (G * L * Hk * d, Hk * d, d, L * Hk * d)
             dk, dv, dp = bk.cuda(), bv.cuda(), pre.cuda()
             for l in range(L):
@@ -204,13 +211,13 @@ def test_strided_input_layer_ranges_and_separate_summary(oqm):
                                       H.bits(pre).ravel()[off:], layer0=l, strides=strides,
                                       n_frames=F, n_layers=1, commit=(l == L - 1))
                 first = oqm.tom_oqm_quantize_append(
-                    mem.handle, l, 1, F, dk.data_ptr() + off * 2, dv.data_ptr() + off * 2,
-                    dp.data_ptr() + off * 2, strides, commit=(l == L - 1))
+                    mem.handle, l, 1, F, dk.data_ptr() + off * eb, dv.data_ptr() + off * eb,
+                    dp.data_ptr() + off * eb, strides, commit=(l == L - 1))
                 assert first == call * F
             torch.cuda.synchronize()
         assert mem.n_groups == 4
         H.compare_storage(st, mem)
-        q = torch.randn(3, 4, 3, 64, generator=g).to(torch.bfloat16)
+        q = torch.randn(3, 4, 3, 64, generator=g).to(tdt)
         H.full_path_check(oqm, st, mem, q, 3)
     finally:
         mem.close()
