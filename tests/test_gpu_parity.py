@@ -358,6 +358,10 @@ def test_both_score_paths_agree(oqm):
         # longer queries than one 64-row tile, and a ragged last row tile
         w2 = synth_kv.scaled(w, t_q=150)
         H.full_path_check(oqm, st, mem, synth_kv.query(w2), 9, oqm.TOM_SCORE_TOKEN_GEMM, True)
+        # every count of 16-row tiles per block (1, 2, 3, 4 and 4 + 1), full and ragged
+        for t_q in (1, 16, 17, 33, 48, 49, 65):
+            wq = synth_kv.scaled(w, t_q=t_q)
+            H.full_path_check(oqm, st, mem, synth_kv.query(wq), 9, oqm.TOM_SCORE_TOKEN_GEMM, True)
     finally:
         mem.close()
 
