@@ -131,9 +131,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="C3", choices=["C2", "C3", "C4", "C5"])
+    ap.add_argument("--workload", default="C3", choices=["C2", "C3", "C4", "C5", "P64"],
+                    help="P64 = the 64-frame stream of the paper's latency breakdown (context figures)")
     ap.add_argument("--frames-per-append", type=int, default=0, help="override the workload's batch")
-    ap.add_argument("--qaxis", default="head_dim", choices=["head_dim", "tokens"],
+    ap.add_argument("--qaxis", default=None, choices=["head_dim", "tokens"],
                     help="tokens = the paper's Eq. 9 (scale/zero per channel over the G tokens)")
     ap.add_argument("--group-tokens", type=int, default=0, help="override G (the paper keeps 50)")
     ap.add_argument("--bits", type=int, default=4, choices=[4, 2], help="code width (2 = the paper's ablation)")
@@ -157,6 +158,8 @@ def main():
     torch.cuda.set_device(0)
     dev = "cuda:0"
     w = synth_kv.WORKLOADS[args.workload]
+    if args.qaxis is None:      # the paper's own stream is quantized the paper's way (Eq. 9)
+        args.qaxis = "tokens" if args.workload == "P64" else "head_dim"
     if args.group_tokens:
         w = synth_kv.scaled(w, group_tokens=args.group_tokens)
     tok = args.qaxis == "tokens"

@@ -45,6 +45,9 @@ WORKLOADS = {
     "C4": Workload("C4", 28, 4, 28, 128, 196, 3600, 64, 32, 64, "bf16", "cosine", 4, "layer_std", 1),
     # outlier-heavy keys, gs 32, 64-token query (dense score contraction)
     "C5": Workload("C5", 28, 4, 28, 128, 196, 1024, 32, 64, 128, "bf16", "cosine", 5, "outlier", 32),
+    # the stream of the paper's latency breakdown (Fig. 5): 64 frames of 50 kept tokens, FP16,
+    # stored 8 frames at a time (the encoder batch), all 64 groups within the 12k-token budget
+    "P64": Workload("P64", 28, 4, 28, 128, 50, 64, 64, 32, 64, "f16", "cosine", 6, "layer_std", 8),
 }
 
 
