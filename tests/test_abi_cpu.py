@@ -229,3 +229,36 @@ def test_product_and_oracle_do_not_reference_each_other():
             assert "paper_2510_18269_amd" not in text and "libtom_oqm" not in text and "tom_oqm.h" not in text, f
     header = open(os.path.join(ROOT, "include", "tom_oqm.h")).read()
     assert "tomref" not in header
+
+
+def test_last_error_is_per_thread(oqm):
+    """tom_last_error returns the message of the calling thread's own last failure."""
+    import threading
+    out = {}
+    barrier = threading.Barrier(2)
+
+    def worker(name, field, value, needle):
+        kw = dict(n_layers=1, n_kv_heads=2, n_q_heads=2, head_dim=64, group_tokens=4, qgroup=32, capacity=2)
+        cfg = oqm.make_config(kw["n_layers"], kw["n_kv_heads"], kw["n_q_heads"], kw["head_dim"],
+                              kw["group_tokens"], kw["qgroup"], kw["capacity"])
+        setattr(cfg, field, value)
+        sizes = oqm.tom_oqm_sizes_t()
+        for _ in range(200):
+            st = oqm.lib.tom_oqm_query_sizes(C.byref(cfg), C.byref(sizes))
+            try:
+                barrier.wait(timeout=30)        # both threads have failed before either reads
+            except threading.BrokenBarrierError:
+                out.setdefault(name, "partner stopped")
+                break
+            msg = oqm.tom_last_error()
+            if st == oqm.TOM_OK or needle not in msg:
+                out[name] = (st, msg)
+                barrier.abort()
+                break
+        else:
+            out[name] = "ok"
+
+    a = threading.Thread(target=worker, args=("a", "head_dim", 12, "head_dim"))
+    b = threading.Thread(target=worker, args=("b", "bits", 3, "bits"))
+    a.start(); b.start(); a.join(); b.join()
+    assert out == {"a": "ok", "b": "ok"}, out
