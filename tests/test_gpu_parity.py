@@ -427,6 +427,50 @@ def test_assemble_with_system_prefix_and_one_call_retrieve(oqm, qaxis, G, prefix
         mem.close()
 
 
+def test_one_call_retrieve_on_an_empty_and_on_a_short_store(oqm):
+    """Nothing stored: k_eff = 0, only the system prefix is written.  Fewer groups stored than
+    asked for: all of them in temporal order, the rows behind them untouched."""
+    w = synth_kv.Workload("X", 2, 2, 4, 64, 9, 3, 32, 5, 6, "bf16", "cosine", 910, "layer_std", 3)
+    st, mem = H.pair_for(oqm, w, capacity=8)
+    try:
+        L, Hk, d, G, k, prefix = w.n_layers, w.n_kv_heads, w.head_dim, w.group_tokens, w.top_k, 2
+        g = torch.Generator().manual_seed(5)
+        sys_k = torch.randn(L, Hk, prefix, d, generator=g).to(torch.bfloat16)
+        sys_v = torch.randn(L, Hk, prefix, d, generator=g).to(torch.bfloat16)
+        q = synth_kv.query(w)
+        rows = prefix + k * G
+        ws = torch.empty(oqm.tom_oqm_score_workspace_bytes(mem.handle, L, w.t_q, oqm.TOM_SCORE_AUTO, False),
+                         dtype=torch.uint8, device="cuda")
+        scores = torch.full((L, 8), 123.0, dtype=torch.float32, device="cuda")
+        idx = torch.full((L, k), -7, dtype=torch.int32, device="cuda")
+
+        def call():
+            ko = torch.zeros((L, Hk, rows, d), dtype=torch.bfloat16, device="cuda")
+            vo = torch.zeros_like(ko)
+            ko.view(torch.int16).fill_(0x7FC1)
+            vo.view(torch.int16).fill_(0x7FC1)
+            ke = oqm.tom_oqm_retrieve(mem.handle, 0, L, q.cuda(), w.t_q, k, scores, 8, idx, ko, vo, ws,
+                                      prefix_rows=prefix, sys_k=sys_k.cuda(), sys_v=sys_v.cuda())
+            torch.cuda.synchronize()
+            return ke, ko, vo
+
+        ke, ko, vo = call()
+        assert ke == 0 and (idx == -7).all() and (scores == 123.0).all()
+        assert np.array_equal(H.bits(ko)[:, :, :prefix], H.bits(sys_k))
+        assert np.all(H.bits(vo)[:, :, prefix:] == 0x7FC1)
+
+        kk, vv = synth_kv.kv_frames(w, 0, 3)
+        H.append_both(oqm, st, mem, kk, vv)
+        ke, ko, vo = call()
+        assert ke == 3 and idx.cpu().numpy()[:, :3].tolist() == [[0, 1, 2]] * L
+        ref_k, ref_v = H.orc.assemble_active(st, idx.cpu().numpy(), 3, prefix, H.bits(sys_k), H.bits(sys_v),
+                                             fill=0x7FC1)
+        assert np.array_equal(H.bits(ko), ref_k) and np.array_equal(H.bits(vo), ref_v)
+        assert np.all(H.bits(ko)[:, :, prefix + 3 * G:] == 0x7FC1)
+    finally:
+        mem.close()
+
+
 def test_layer_by_layer_calls_match_the_all_layer_call(oqm):
     """Inside a model's forward pass the retrieval runs one layer at a time (layer0 = l,
     n_layers = 1): every step must give what the all-layer call gives, i.e. the oracle's."""
