@@ -61,6 +61,28 @@ def measured_traffic(kernel, workload):
     return None
 
 
+def load_probe_lib():
+    """The benchmark-only shared object (stream probes, timing events); not part of the library."""
+    import ctypes as C
+    path = os.path.join(ROOT, "paper_2510_18269_amd", "libtom_bench_probe.so")
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} is missing: build first (python -m paper_2510_18269_amd.build)")
+    lib = C.CDLL(path)
+    lib.bench_stream_probe.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+    lib.bench_stream_probe.restype = C.c_int
+    lib.bench_event_create.argtypes = [C.c_int32]
+    lib.bench_event_create.restype = C.c_void_p
+    lib.bench_event_record.argtypes = [C.c_void_p, C.c_void_p]
+    lib.bench_event_record.restype = C.c_int
+    lib.bench_event_synchronize.argtypes = [C.c_void_p]
+    lib.bench_event_synchronize.restype = C.c_int
+    lib.bench_event_elapsed_ms.argtypes = [C.c_void_p, C.c_void_p]
+    lib.bench_event_elapsed_ms.restype = C.c_float
+    lib.bench_event_destroy.argtypes = [C.c_void_p]
+    lib.bench_event_destroy.restype = None
+    return lib
+
+
 def cpu_baseline(w, batches_cpu, q_cpu, threads, qaxis=0, bits=4, meta="f32"):
     """The oracle, as it stands, on a bounded sample of the same workload: the given append
     batches (all layers) and one retrieval over what they stored.  Threads split layers."""
@@ -247,6 +269,8 @@ def main():
 
     # what the machine reaches for the byte mix of the two big kernels: the library's
     # arithmetic-free stream probes over rotating regions far larger than the last-level cache
+    probe_lib = load_probe_lib()
+
     def probe(mode, read_b, write_b):
         items = 44 << 20
         n_src, n_dst = (12, 4) if read_b < write_b else (4, 12)
@@ -257,8 +281,10 @@ def main():
         for i in range(3 + reps):
             if i == 3:
                 ev[0].record()
-            oqm.tom_oqm_stream_probe(mode, src.data_ptr() + (i % n_src) * items * read_b,
-                                     dst.data_ptr() + (i % n_dst) * items * write_b, items)
+            rc = probe_lib.bench_stream_probe(mode, src.data_ptr() + (i % n_src) * items * read_b,
+                                              dst.data_ptr() + (i % n_dst) * items * write_b, items,
+                                              torch.cuda.current_stream().cuda_stream)
+            assert rc == 0, f"stream probe: hipError {rc}"
         ev[1].record()
         torch.cuda.synchronize()
         return reps * items * (read_b + write_b) / (ev[0].elapsed_time(ev[1]) * 1e-3) / 1e9

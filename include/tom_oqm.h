@@ -86,10 +86,12 @@ typedef enum {
 
 typedef struct {
     int32_t n_layers;        /* L                                                        */
-    int32_t n_kv_heads;      /* H_k                                                      */
+    int32_t n_kv_heads;      /* H_k; H_k * d <= 8192 (the score kernels stage the folded
+                                query of a layer, H_k * d float64, in 64 KB of LDS)      */
     int32_t n_q_heads;       /* H_q, a multiple of H_k (GQA blocks of consecutive heads) */
     int32_t head_dim;        /* d, a multiple of 8, at most 2048                         */
-    int32_t group_tokens;    /* G >= 1, tokens per frame-group                           */
+    int32_t group_tokens;    /* G >= 1, tokens per frame-group; (G + 1024) * d * 4 must
+                                stay below 2 GiB (offsets inside one head tile are 32-bit) */
     int32_t qgroup;          /* gs in {8, 16, 32, 64, 128}, divides d (HEAD_DIM axis);
                                 ignored on the TOKENS axis                               */
     int32_t qaxis;           /* tom_qaxis_t                                              */
@@ -174,8 +176,10 @@ int32_t tom_oqm_k_from_budget(int64_t budget_tokens, int32_t group_tokens, int32
  *
  * Errors: INVALID_ARG (NULL k/v, bad layer range, n_frames < 0, misaligned
  * pointer or stride), CAPACITY (T + n_frames > capacity_groups; nothing is
- * evicted), NOT_BOUND, UNSUPPORTED, HIP.  n_frames == 0 or n_layers == 0 is a
- * successful no-op.
+ * evicted), NOT_BOUND, UNSUPPORTED (more than 65535 frames or 32767 layers in one
+ * call; a token stride so large that one head tile, (G + 1024) * strides[3]
+ * elements, spans 2 GiB or more), HIP.  n_frames == 0 or n_layers == 0 is a
+ * successful no-op.  first_group is written by successful calls only.
  */
 tom_status_t tom_oqm_quantize_append(tom_oqm_t* h, int32_t layer0, int32_t n_layers,
                                      int32_t n_frames, const void* k_device,
@@ -206,7 +210,8 @@ size_t tom_oqm_score_workspace_bytes(const tom_oqm_t* h, int32_t n_layers, int32
  *   workspace     device, 16-byte aligned, at least
  *                 tom_oqm_score_workspace_bytes(...) bytes; scratch, contents
  *                 undefined afterwards; concurrent calls need separate ones.
- * Errors: INVALID_ARG, NOT_BOUND, UNSUPPORTED, HIP.  T == 0 is a no-op.
+ * Errors: INVALID_ARG, NOT_BOUND, UNSUPPORTED (more than 65535 layers per call),
+ * HIP.  T == 0 is a no-op.
  */
 tom_status_t tom_oqm_score_groups(const tom_oqm_t* h, int32_t layer0, int32_t n_layers,
                                   const void* q_device, int32_t q_dtype, int32_t t_q,
@@ -225,7 +230,8 @@ tom_status_t tom_oqm_score_groups(const tom_oqm_t* h, int32_t layer0, int32_t n_
  *   idx         device int32 [n_rows][k]
  *   k_eff_host  host, may be NULL: receives k_eff (known without a sync)
  * Errors: INVALID_ARG (k < 1, n_groups < 0, stride < n_groups, NULL),
- * UNSUPPORTED (SCORE_DESC with k_eff > 4096), HIP.
+ * UNSUPPORTED (SCORE_DESC with k_eff > 4096), HIP.  k_eff_host is written by
+ * successful calls only.
  */
 tom_status_t tom_oqm_topk(const float* scores_device, int64_t score_stride, int32_t n_rows,
                           int32_t n_groups, int32_t k, int32_t order, int32_t* idx_device,
@@ -244,7 +250,8 @@ tom_status_t tom_oqm_topk(const float* scores_device, int64_t score_stride, int3
  *                 aligned.  Rows >= k_eff * G are never written: the active
  *                 buffer is bounded by k * G tokens per layer whatever T is.
  * An index outside [0, T) is skipped by the kernel (its rows stay untouched).
- * Errors: INVALID_ARG, NOT_BOUND, UNSUPPORTED, HIP.  k_eff == 0 is a no-op.
+ * Errors: INVALID_ARG, NOT_BOUND, UNSUPPORTED (more than 65535 layers per call
+ * or more than 32767 KV heads), HIP.  k_eff == 0 is a no-op.
  */
 tom_status_t tom_oqm_dequant_gather(const tom_oqm_t* h, int32_t layer0, int32_t n_layers,
                                     const int32_t* idx_device, int32_t k, int32_t k_eff,
@@ -263,7 +270,7 @@ tom_status_t tom_oqm_dequant_gather(const tom_oqm_t* h, int32_t layer0, int32_t 
  *                 model's 16-bit format: they are copied, not re-quantized), or both NULL
  *                 to leave rows [0, prefix_rows) as they are (e.g. written once per session).
  * Errors as for tom_oqm_dequant_gather; prefix_rows < 0 or only one of sys_k / sys_v given
- * is INVALID_ARG.
+ * is INVALID_ARG; with a prefix source, H_k * n_layers > 65535 is UNSUPPORTED.
  */
 tom_status_t tom_oqm_assemble_active(const tom_oqm_t* h, int32_t layer0, int32_t n_layers,
                                      const int32_t* idx_device, int32_t k, int32_t k_eff,
@@ -289,21 +296,6 @@ tom_status_t tom_oqm_retrieve(const tom_oqm_t* h, int32_t layer0, int32_t n_laye
                               const void* sys_v_device, void* k_out_device, void* v_out_device,
                               void* workspace_device, size_t workspace_bytes, int32_t* k_eff_host,
                               void* hip_stream);
-
-/*
- * Measurement aid, not a step of the method (the supplement's implementation paragraphs
- * give timings only; this is what lets a benchmark put a measured machine ceiling beside
- * them): streams `items` units from src to dst with no arithmetic, one unit per thread,
- * linear and coalesced, in the byte mix of one of the bandwidth-bound steps.
- *   mode 0  reads  4 B, writes 16 B per item   (dequant-gather's mix)
- *   mode 1  reads 16 B, writes  4 B per item   (quantize-append's mix)
- *   mode 2  reads 16 B, writes 16 B per item   (copy)
- *   src, dst  device, 16-byte aligned, items * (bytes read / written per item) large;
- *             dst receives values derived from src (not a copy in modes 0 and 1).
- * Errors: mode outside 0..2, items < 0, NULL or misaligned pointers -> INVALID_ARG.
- */
-tom_status_t tom_oqm_stream_probe(int32_t mode, const void* src_device, void* dst_device,
-                                  int64_t items, void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -13,14 +13,17 @@ LIB = os.path.join(HERE, "libtom_oqm.so")
 OBJ = os.path.join(HERE, "_build")
 SELFCHECK = os.path.join(HERE, "selfcheck_division.bin")
 
-SOURCES = ["oqm_api.hip", "oqm_quantize.hip", "oqm_quantize_tokens.hip", "oqm_dequant.hip", "oqm_score.hip", "oqm_topk.hip",
-           "oqm_probe.hip"]
+SOURCES = ["oqm_api.hip", "oqm_quantize.hip", "oqm_quantize_tokens.hip", "oqm_dequant.hip", "oqm_score.hip",
+           "oqm_topk.hip"]
+# benchmark-only helpers (stream probes, timing events): a shared object of their own that only
+# bench.py loads; nothing of it is in the library or in its ABI header
+BENCH_LIB = os.path.join(HERE, "libtom_bench_probe.so")
 
 # -ffp-contract=off: the codes, scale/zero and dequantized values must be single, separately
 # rounded IEEE operations.  -fno-honor-nans (inputs are finite by contract) only lets min/max
 # compile to one instruction each; it changes no result on finite data.
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
-          "-fno-honor-nans", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+          "-fno-honor-nans", "-fvisibility=hidden", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
           "-Wall", "-Wno-unused-result", "-I", INCLUDE, "-I", CSRC]
 
 
@@ -49,6 +52,10 @@ def build(verbose: bool = False) -> str:
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"link failed:\n{r.stdout}\n{r.stderr}")
+    cmd = ["hipcc", *COMMON, "-shared", os.path.join(CSRC, "bench_probe.hip"), "-o", BENCH_LIB]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"bench probe build failed:\n{r.stdout}\n{r.stderr}")
     # stand-alone GPU program that checks the kernels' division shortcuts exhaustively
     cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-ffp-contract=off",
            "-Wno-unused-result", "-I", INCLUDE, "-I", CSRC,

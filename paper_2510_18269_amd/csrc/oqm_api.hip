@@ -60,6 +60,11 @@ static tom_status_t check_config(const tom_oqm_config_t* c) {
     return TOM_OK;
 }
 
+// The launchers report hipGetLastError() after their launch.  An error that an unrelated,
+// earlier HIP call of the process left behind must not be taken for this launch's: read it
+// away first (reading resets it).
+static void drop_stale_hip_error() { (void)hipGetLastError(); }
+
 static tom_status_t check_layers(const tom_oqm_t* h, int32_t layer0, int32_t n_layers) {
     if (layer0 < 0 || n_layers < 0 || (int64_t)layer0 + n_layers > h->cfg.n_layers)
         return fail(TOM_ERR_INVALID_ARG, "layer range [%d, %d) is outside [0, %d)", layer0,
@@ -147,8 +152,10 @@ tom_status_t tom_oqm_quantize_append(tom_oqm_t* h, int32_t layer0, int32_t n_lay
     if ((int64_t)h->n_groups + n_frames > h->cfg.capacity_groups)
         return fail(TOM_ERR_CAPACITY, "%d stored + %d new frame-groups exceed capacity %d",
                     h->n_groups, n_frames, h->cfg.capacity_groups);
-    if (first_group) *first_group = h->n_groups;
-    if (n_frames == 0 || n_layers == 0) return TOM_OK;
+    if (n_frames == 0 || n_layers == 0) {
+        if (first_group) *first_group = h->n_groups;
+        return TOM_OK;
+    }
     if (!k || !v || !strides) return fail(TOM_ERR_INVALID_ARG, "k, v and strides must be non-NULL");
     const tom_oqm_config_t& c = h->cfg;
     const int eb = dtype_bytes(c.in_dtype);
@@ -188,8 +195,10 @@ tom_status_t tom_oqm_quantize_append(tom_oqm_t* h, int32_t layer0, int32_t n_lay
     a.qaxis = c.qaxis;
     a.bits = c.bits;
     a.meta_bf16 = c.meta_dtype == TOM_BF16;
+    drop_stale_hip_error();
     const hipError_t e = launch_quantize_append(a, c.in_dtype, static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return fail(TOM_ERR_HIP, "quantize_append launch: %s", hipGetErrorString(e));
+    if (first_group) *first_group = h->n_groups;  // only a call that succeeds writes its output
     if (commit) h->n_groups += n_frames;
     return TOM_OK;
 }
@@ -264,11 +273,10 @@ static tom_status_t score_impl(const tom_oqm_t* h, int32_t layer0, int32_t n_lay
     a.sim = c.sim;
     a.q_dtype = q_dtype;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    drop_stale_hip_error();
     hipError_t e = launch_query_fold(a, rpath == TOM_SCORE_TOKEN_GEMM, s);
     if (e != hipSuccess) return fail(TOM_ERR_HIP, "query_fold launch: %s", hipGetErrorString(e));
     e = rpath == TOM_SCORE_TOKEN_GEMM ? launch_score_token_gemm(a, s) : launch_score_mean_query(a, s);
-    if (e == hipErrorNotSupported)
-        return fail(TOM_ERR_UNSUPPORTED, "this score path is not built for the given shape");
     if (e != hipSuccess) return fail(TOM_ERR_HIP, "score launch: %s", hipGetErrorString(e));
     return TOM_OK;
 }
@@ -292,10 +300,12 @@ static tom_status_t topk_impl(const float* scores, int64_t score_stride, int32_t
     const int k_eff = k < n_groups ? k : n_groups;
     if (order == TOM_ORDER_SCORE_DESC && k_eff > kTopkMaxSortedK)
         return fail(TOM_ERR_UNSUPPORTED, "TOM_ORDER_SCORE_DESC supports k_eff <= %d", kTopkMaxSortedK);
+    if ((n_rows > 0 && k_eff > 0) && (!scores || !idx))
+        return fail(TOM_ERR_INVALID_ARG, "scores and idx must be non-NULL");
+    if (!launch) return TOM_OK;  // validation pass of the one-call retrieval: no output yet
     if (k_eff_host) *k_eff_host = k_eff;
     if (n_rows == 0 || k_eff == 0) return TOM_OK;
-    if (!scores || !idx) return fail(TOM_ERR_INVALID_ARG, "scores and idx must be non-NULL");
-    if (!launch) return TOM_OK;
+    drop_stale_hip_error();
     const hipError_t e = launch_topk(scores, score_stride, n_rows, n_groups, k, k_eff, order, idx,
                                      static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return fail(TOM_ERR_HIP, "topk launch: %s", hipGetErrorString(e));
@@ -329,6 +339,14 @@ static tom_status_t assemble_impl(const tom_oqm_t* h, int32_t layer0, int32_t n_
     const tom_oqm_config_t& c = h->cfg;
     if (2 * c.n_kv_heads > 65535 || n_layers > 65535)
         return fail(TOM_ERR_UNSUPPORTED, "at most 32767 KV heads and 65535 layers per call");
+    if (copy_prefix) {  // grid of the prefix copy: (16-byte chunks / 256, H_k * n_layers, 2)
+        const int64_t prefix_bytes = (int64_t)prefix_rows * c.head_dim * dtype_bytes(c.out_dtype);
+        if ((int64_t)c.n_kv_heads * n_layers > 65535)
+            return fail(TOM_ERR_UNSUPPORTED, "prefix copy: n_kv_heads * n_layers = %lld exceeds 65535",
+                        (long long)c.n_kv_heads * n_layers);
+        if ((prefix_bytes / 16 + kBlock - 1) / kBlock > 0x7fffffffLL)
+            return fail(TOM_ERR_UNSUPPORTED, "prefix copy: prefix_rows * head_dim is too large");
+    }
     if (!launch) return TOM_OK;
     DequantArgs a;
     a.codes = h->codes;
@@ -351,6 +369,7 @@ static tom_status_t assemble_impl(const tom_oqm_t* h, int32_t layer0, int32_t n_
     a.meta_bf16 = c.meta_dtype == TOM_BF16;
     a.prefix_rows = prefix_rows;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    drop_stale_hip_error();
     if (copy_prefix) {
         const hipError_t e = launch_prefix_copy(a, sys_k, sys_v, c.out_dtype, s);
         if (e != hipSuccess) return fail(TOM_ERR_HIP, "prefix copy launch: %s", hipGetErrorString(e));
@@ -396,18 +415,6 @@ tom_status_t tom_oqm_retrieve(const tom_oqm_t* h, int32_t layer0, int32_t n_laye
                                             prefix_rows, sys_k, sys_v, k_out, v_out, hip_stream, go))
             return st;
     }
-    return TOM_OK;
-}
-
-tom_status_t tom_oqm_stream_probe(int32_t mode, const void* src, void* dst, int64_t items,
-                                  void* hip_stream) {
-    if (mode < 0 || mode > 2) return fail(TOM_ERR_INVALID_ARG, "mode must be 0, 1 or 2");
-    if (items < 0) return fail(TOM_ERR_INVALID_ARG, "items < 0");
-    if (items == 0) return TOM_OK;
-    if (!src || !dst || !aligned16(src) || !aligned16(dst))
-        return fail(TOM_ERR_INVALID_ARG, "src and dst must be non-NULL and 16-byte aligned");
-    const hipError_t e = launch_stream_probe(mode, src, dst, items, static_cast<hipStream_t>(hip_stream));
-    if (e != hipSuccess) return fail(TOM_ERR_HIP, "stream probe launch: %s", hipGetErrorString(e));
     return TOM_OK;
 }
 

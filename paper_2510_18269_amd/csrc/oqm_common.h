@@ -5,7 +5,11 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+// The library is built with hidden visibility: only the functions of the ABI header are
+// exported from the shared object.
+#pragma GCC visibility push(default)
 #include "tom_oqm.h"
+#pragma GCC visibility pop
 
 struct tom_oqm {
     tom_oqm_config_t cfg;
@@ -91,7 +95,6 @@ hipError_t launch_prefix_copy(const DequantArgs& a, const void* sys_k, const voi
 hipError_t launch_query_fold(const ScoreArgs& a, bool want_tokens, hipStream_t s);
 hipError_t launch_score_mean_query(const ScoreArgs& a, hipStream_t s);
 hipError_t launch_score_token_gemm(const ScoreArgs& a, hipStream_t s);
-hipError_t launch_stream_probe(int mode, const void* src, void* dst, int64_t items, hipStream_t s);
 hipError_t launch_topk(const float* scores, int64_t stride, int n_rows, int n_groups, int k,
                        int k_eff, int order, int32_t* idx, hipStream_t s);
 

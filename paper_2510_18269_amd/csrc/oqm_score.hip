@@ -210,10 +210,7 @@ __global__ void __launch_bounds__(kBlock) score_mean_query_kernel(const ScoreArg
 // 16*g + j holds D[4*v + g][j] in accumulator register v.
 constexpr int kGemmN = 64;
 constexpr int kGemmM = 64;
-#ifndef OQM_GEMM_K
-#define OQM_GEMM_K 32
-#endif
-constexpr int kGemmK = OQM_GEMM_K;
+constexpr int kGemmK = 32;
 // Row pitches of the staged operands.  A fragment read takes element (row fi, column kk) per
 // lane: with 34 doubles per row the 32 lanes of a half-wave fall on 4*fi + 2*kk, i.e. on all
 // 32 even banks once (a pitch of 36 puts rows fi and fi + 8 on the same banks: measured 9 %

@@ -31,7 +31,7 @@ EXPORTS = ["tom_oqm_query_sizes", "tom_oqm_create", "tom_oqm_bind", "tom_oqm_res
            "tom_oqm_num_groups", "tom_oqm_set_num_groups", "tom_oqm_destroy", "tom_last_error",
            "tom_oqm_k_from_budget", "tom_oqm_quantize_append", "tom_oqm_score_workspace_bytes",
            "tom_oqm_score_groups", "tom_oqm_topk", "tom_oqm_dequant_gather",
-           "tom_oqm_assemble_active", "tom_oqm_retrieve", "tom_oqm_stream_probe"]
+           "tom_oqm_assemble_active", "tom_oqm_retrieve"]
 
 
 class TomError(RuntimeError):
@@ -80,7 +80,6 @@ def _load():
     L.tom_oqm_assemble_active.argtypes = [vp, i32, i32, vp, i32, i32, i32, vp, vp, vp, vp, vp]
     L.tom_oqm_retrieve.argtypes = [vp, i32, i32, vp, i32, i32, i32, i32, vp, i64, vp, i32, vp, vp,
                                    vp, vp, vp, C.c_size_t, C.POINTER(i32), vp]
-    L.tom_oqm_stream_probe.argtypes = [i32, vp, vp, i64, vp]
     for name in EXPORTS:
         fn = getattr(L, name)
         if name not in ("tom_oqm_destroy", "tom_last_error", "tom_oqm_score_workspace_bytes"):
@@ -228,10 +227,6 @@ def tom_oqm_retrieve(h: int, layer0: int, n_layers: int, q, t_q: int, k: int, sc
                                 _ptr(k_out), _ptr(v_out), _ptr(workspace), ws_bytes,
                                 C.byref(k_eff), _stream(stream)))
     return k_eff.value
-
-
-def tom_oqm_stream_probe(mode: int, src, dst, items: int, stream=None) -> None:
-    _check(lib.tom_oqm_stream_probe(mode, _ptr(src), _ptr(dst), items, _stream(stream)))
 
 
 # --------------------------------------------------------------------------- convenience
