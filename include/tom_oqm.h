@@ -297,6 +297,33 @@ tom_status_t tom_oqm_retrieve(const tom_oqm_t* h, int32_t layer0, int32_t n_laye
                               void* workspace_device, size_t workspace_bytes, int32_t* k_eff_host,
                               void* hip_stream);
 
+/*
+ * tom_oqm_retrieve for callers that cannot allocate device memory and have no workspace to
+ * hand over: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same steps, same kernels, same results as tom_oqm_retrieve; the score step's
+ * scratch lives in a fixed device array inside the library (tom_oqm_static_scratch_bytes()
+ * = 8 MiB, held on every GPU the library runs on until the process ends).  The call
+ * allocates and frees nothing.  The array's device address is looked up at the first call
+ * on each device (no allocation; make that first call outside a graph capture).
+ *   - Shapes whose scratch (tom_oqm_score_workspace_bytes of the same n_layers, t_q, path)
+ *     exceeds the array are refused with UNSUPPORTED before anything is queued: 8 MiB
+ *     covers 28 layers x 64 query tokens x 512 flattened key channels on the TOKEN_GEMM path
+ *     and any realistic shape on the MEAN_QUERY path.
+ *   - All calls on one GPU share that GPU's array: two calls whose kernels may overlap
+ *     (different streams, or two threads) race on it.  Calls on one stream are safe.
+ *     Nothing in the array has to start at zero; every call overwrites what it reads.
+ * Other arguments, outputs and errors as for tom_oqm_retrieve.
+ */
+tom_status_t tom_oqm_retrieve_noalloc(const tom_oqm_t* h, int32_t layer0, int32_t n_layers,
+                                      const void* q_device, int32_t q_dtype, int32_t t_q, int32_t k,
+                                      int32_t path, float* scores_device, int64_t score_stride,
+                                      int32_t* idx_device, int32_t prefix_rows,
+                                      const void* sys_k_device, const void* sys_v_device,
+                                      void* k_out_device, void* v_out_device, int32_t* k_eff_host,
+                                      void* hip_stream);
+/* Size in bytes of the static scratch array tom_oqm_retrieve_noalloc works in. */
+size_t tom_oqm_static_scratch_bytes(void);
+
 #ifdef __cplusplus
 }
 #endif

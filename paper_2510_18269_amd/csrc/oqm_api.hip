@@ -4,6 +4,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "oqm_common.h"
@@ -69,6 +70,36 @@ static tom_status_t check_layers(const tom_oqm_t* h, int32_t layer0, int32_t n_l
     if (layer0 < 0 || n_layers < 0 || (int64_t)layer0 + n_layers > h->cfg.n_layers)
         return fail(TOM_ERR_INVALID_ARG, "layer range [%d, %d) is outside [0, %d)", layer0,
                     layer0 + n_layers, h->cfg.n_layers);
+    return TOM_OK;
+}
+
+// ---- scratch memory of the entry point that allocates nothing ---------------------------
+// The score step's scratch (folded query, its squared norms, the per-token query block of
+// the matrix-core path) for callers that can neither allocate nor hand over a workspace.
+// The array's name is only a host-side stand-in: its device address is looked up once per
+// device (each GPU holds its own copy) and that pointer is what the kernels get.
+constexpr size_t kScratchBytes = size_t{8} << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[kMaxDevices] = {};
+
+static tom_status_t static_scratch_of_current_device(void** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(TOM_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices)
+        return fail(TOM_ERR_UNSUPPORTED, "device ordinal %d is outside [0, %d)", dev, kMaxDevices);
+    std::lock_guard<std::mutex> guard(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p)
+            return fail(TOM_ERR_HIP, "hipGetSymbolAddress(scratch) on device %d: %s", dev, hipGetErrorString(e));
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
     return TOM_OK;
 }
 
@@ -394,6 +425,26 @@ tom_status_t tom_oqm_assemble_active(const tom_oqm_t* h, int32_t layer0, int32_t
                          hip_stream, true);
 }
 
+// One pass of the one-call retrieval over its three steps: validation only (go == false),
+// or validation and launch.
+static tom_status_t retrieve_pass(const tom_oqm_t* h, int32_t layer0, int32_t n_layers, const void* q,
+                                  int32_t q_dtype, int32_t t_q, int32_t k, int32_t path, float* scores,
+                                  int64_t score_stride, int32_t* idx, int32_t prefix_rows,
+                                  const void* sys_k, const void* sys_v, void* k_out, void* v_out,
+                                  void* workspace, size_t workspace_bytes, int32_t* k_eff_host,
+                                  void* hip_stream, bool go) {
+    const int T = h->n_groups;
+    const int k_eff = k < T ? k : T;
+    if (tom_status_t st = score_impl(h, layer0, n_layers, q, q_dtype, t_q, scores, score_stride, nullptr,
+                                     path, workspace, workspace_bytes, hip_stream, go))
+        return st;
+    if (tom_status_t st = topk_impl(scores, score_stride, n_layers, T, k, TOM_ORDER_INDEX_ASC, idx,
+                                    k_eff_host, hip_stream, go))
+        return st;
+    return assemble_impl(h, layer0, n_layers, idx, k, k_eff < 0 ? 0 : k_eff, prefix_rows, sys_k, sys_v,
+                         k_out, v_out, hip_stream, go);
+}
+
 tom_status_t tom_oqm_retrieve(const tom_oqm_t* h, int32_t layer0, int32_t n_layers, const void* q,
                               int32_t q_dtype, int32_t t_q, int32_t k, int32_t path, float* scores,
                               int64_t score_stride, int32_t* idx, int32_t prefix_rows,
@@ -401,21 +452,42 @@ tom_status_t tom_oqm_retrieve(const tom_oqm_t* h, int32_t layer0, int32_t n_laye
                               void* workspace, size_t workspace_bytes, int32_t* k_eff_host,
                               void* hip_stream) {
     if (!h) return fail(TOM_ERR_INVALID_ARG, "handle is NULL");
-    const int T = h->n_groups;
-    const int k_eff = k < T ? k : T;
-    for (int pass = 0; pass < 2; ++pass) {  // pass 0 validates all three steps, pass 1 launches them
-        const bool go = pass == 1;
-        if (tom_status_t st = score_impl(h, layer0, n_layers, q, q_dtype, t_q, scores, score_stride,
-                                         nullptr, path, workspace, workspace_bytes, hip_stream, go))
+    for (int pass = 0; pass < 2; ++pass)  // pass 0 validates all three steps, pass 1 launches them
+        if (tom_status_t st = retrieve_pass(h, layer0, n_layers, q, q_dtype, t_q, k, path, scores,
+                                            score_stride, idx, prefix_rows, sys_k, sys_v, k_out, v_out,
+                                            workspace, workspace_bytes, k_eff_host, hip_stream, pass == 1))
             return st;
-        if (tom_status_t st = topk_impl(scores, score_stride, n_layers, T, k, TOM_ORDER_INDEX_ASC, idx,
-                                        k_eff_host, hip_stream, go))
-            return st;
-        if (tom_status_t st = assemble_impl(h, layer0, n_layers, idx, k, k_eff < 0 ? 0 : k_eff,
-                                            prefix_rows, sys_k, sys_v, k_out, v_out, hip_stream, go))
-            return st;
-    }
     return TOM_OK;
+}
+
+size_t tom_oqm_static_scratch_bytes(void) { return kScratchBytes; }
+
+tom_status_t tom_oqm_retrieve_noalloc(const tom_oqm_t* h, int32_t layer0, int32_t n_layers,
+                                      const void* q, int32_t q_dtype, int32_t t_q, int32_t k,
+                                      int32_t path, float* scores, int64_t score_stride, int32_t* idx,
+                                      int32_t prefix_rows, const void* sys_k, const void* sys_v,
+                                      void* k_out, void* v_out, int32_t* k_eff_host, void* hip_stream) {
+    if (!h) return fail(TOM_ERR_INVALID_ARG, "handle is NULL");
+    // Size check and full validation first, on the host alone (a stand-in pointer takes the
+    // workspace's place): a call that fails here has not touched the GPU.
+    const size_t need = tom_oqm_score_workspace_bytes(h, n_layers < 0 ? 0 : n_layers, t_q < 1 ? 1 : t_q,
+                                                      resolve_path(path, false), 0);
+    if (need > kScratchBytes)
+        return fail(TOM_ERR_UNSUPPORTED,
+                    "the score step needs %zu bytes of scratch for %d layers and a %d-token query; the "
+                    "library's static scratch array holds %zu (use tom_oqm_retrieve with a workspace)",
+                    need, n_layers, t_q, kScratchBytes);
+    void* const stand_in = reinterpret_cast<void*>(uintptr_t{256});
+    if (tom_status_t st = retrieve_pass(h, layer0, n_layers, q, q_dtype, t_q, k, path, scores, score_stride,
+                                        idx, prefix_rows, sys_k, sys_v, k_out, v_out, stand_in,
+                                        kScratchBytes, k_eff_host, hip_stream, false))
+        return st;
+    void* ws = stand_in;  // an empty store or layer range launches no kernel that uses scratch
+    if (h->n_groups > 0 && n_layers > 0)
+        if (tom_status_t st = static_scratch_of_current_device(&ws)) return st;
+    return retrieve_pass(h, layer0, n_layers, q, q_dtype, t_q, k, path, scores, score_stride, idx,
+                         prefix_rows, sys_k, sys_v, k_out, v_out, ws, kScratchBytes, k_eff_host,
+                         hip_stream, true);
 }
 
 }  // extern "C"

@@ -31,7 +31,8 @@ EXPORTS = ["tom_oqm_query_sizes", "tom_oqm_create", "tom_oqm_bind", "tom_oqm_res
            "tom_oqm_num_groups", "tom_oqm_set_num_groups", "tom_oqm_destroy", "tom_last_error",
            "tom_oqm_k_from_budget", "tom_oqm_quantize_append", "tom_oqm_score_workspace_bytes",
            "tom_oqm_score_groups", "tom_oqm_topk", "tom_oqm_dequant_gather",
-           "tom_oqm_assemble_active", "tom_oqm_retrieve"]
+           "tom_oqm_assemble_active", "tom_oqm_retrieve", "tom_oqm_retrieve_noalloc",
+           "tom_oqm_static_scratch_bytes"]
 
 
 class TomError(RuntimeError):
@@ -80,9 +81,14 @@ def _load():
     L.tom_oqm_assemble_active.argtypes = [vp, i32, i32, vp, i32, i32, i32, vp, vp, vp, vp, vp]
     L.tom_oqm_retrieve.argtypes = [vp, i32, i32, vp, i32, i32, i32, i32, vp, i64, vp, i32, vp, vp,
                                    vp, vp, vp, C.c_size_t, C.POINTER(i32), vp]
+    L.tom_oqm_retrieve_noalloc.argtypes = [vp, i32, i32, vp, i32, i32, i32, i32, vp, i64, vp, i32, vp,
+                                           vp, vp, vp, C.POINTER(i32), vp]
+    L.tom_oqm_static_scratch_bytes.argtypes = []
+    L.tom_oqm_static_scratch_bytes.restype = C.c_size_t
     for name in EXPORTS:
         fn = getattr(L, name)
-        if name not in ("tom_oqm_destroy", "tom_last_error", "tom_oqm_score_workspace_bytes"):
+        if name not in ("tom_oqm_destroy", "tom_last_error", "tom_oqm_score_workspace_bytes",
+                        "tom_oqm_static_scratch_bytes"):
             fn.restype = i32
     return L
 
@@ -227,6 +233,25 @@ def tom_oqm_retrieve(h: int, layer0: int, n_layers: int, q, t_q: int, k: int, sc
                                 _ptr(k_out), _ptr(v_out), _ptr(workspace), ws_bytes,
                                 C.byref(k_eff), _stream(stream)))
     return k_eff.value
+
+
+def tom_oqm_retrieve_noalloc(h: int, layer0: int, n_layers: int, q, t_q: int, k: int, scores,
+                             score_stride: int, idx, k_out, v_out, path: int = TOM_SCORE_AUTO,
+                             prefix_rows: int = 0, sys_k=None, sys_v=None, stream=None,
+                             q_dtype: int | None = None) -> int:
+    """tom_oqm_retrieve without a workspace: the score scratch is the library's static array."""
+    if q_dtype is None:
+        q_dtype = _DTYPE_OF_TORCH[q.dtype]
+    k_eff = C.c_int32(-1)
+    _check(lib.tom_oqm_retrieve_noalloc(h, layer0, n_layers, _ptr(q), q_dtype, t_q, k, path,
+                                        _ptr(scores), score_stride, _ptr(idx), prefix_rows,
+                                        _ptr(sys_k), _ptr(sys_v), _ptr(k_out), _ptr(v_out),
+                                        C.byref(k_eff), _stream(stream)))
+    return k_eff.value
+
+
+def tom_oqm_static_scratch_bytes() -> int:
+    return lib.tom_oqm_static_scratch_bytes()
 
 
 # --------------------------------------------------------------------------- convenience

@@ -147,6 +147,35 @@ def test_assemble_and_retrieve_validation(oqm):
         oqm.tom_oqm_destroy(h)
 
 
+def test_retrieve_noalloc_checks_sizes_and_arguments_on_the_host(oqm):
+    """The entry point that allocates nothing: its scratch limit and the validation of all
+    three steps are host-side and come before the first GPU call."""
+    assert oqm.tom_oqm_static_scratch_bytes() == 8 << 20
+    cfg = oqm.make_config(2, 4, 28, 128, 16, 64, 8)
+    h = oqm.tom_oqm_create(cfg)
+    try:
+        fake = 0x1000
+        oqm.tom_oqm_bind(h, fake, fake, fake)
+        # empty store: k_eff = 0, nothing launched, the scratch is not even looked up
+        assert oqm.tom_oqm_retrieve_noalloc(h, 0, 2, fake, 1, 4, fake, 8, fake, fake, fake,
+                                            q_dtype=oqm.TOM_F32) == 0
+        oqm.tom_oqm_set_num_groups(h, 8)
+        # 2 layers x 2048 query tokens x 512 channels of float64 = 16 MiB on the matrix-core path
+        assert oqm.tom_oqm_score_workspace_bytes(h, 2, 2048, oqm.TOM_SCORE_TOKEN_GEMM) > 8 << 20
+        with pytest.raises(oqm.TomError) as e:
+            oqm.tom_oqm_retrieve_noalloc(h, 0, 2, fake, 2048, 4, fake, 8, fake, fake, fake,
+                                         path=oqm.TOM_SCORE_TOKEN_GEMM, q_dtype=oqm.TOM_F32)
+        assert e.value.status == oqm.TOM_ERR_UNSUPPORTED and "static scratch" in str(e.value)
+        # the same query on the mean-query path fits; the missing k_out is then found by the
+        # validation pass, before any device is asked for the array's address
+        with pytest.raises(oqm.TomError) as e:
+            oqm.tom_oqm_retrieve_noalloc(h, 0, 2, fake, 2048, 4, fake, 8, fake, None, fake,
+                                         path=oqm.TOM_SCORE_MEAN_QUERY, q_dtype=oqm.TOM_F32)
+        assert e.value.status == oqm.TOM_ERR_INVALID_ARG and "k_out" in str(e.value)
+    finally:
+        oqm.tom_oqm_destroy(h)
+
+
 def test_two_bit_sizes(oqm):
     cfg = oqm.make_config(28, 4, 28, 128, 50, 64, 100, bits=2)
     s = oqm.tom_oqm_query_sizes(cfg)
