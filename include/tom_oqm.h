@@ -177,7 +177,7 @@ int32_t tom_oqm_k_from_budget(int64_t budget_tokens, int32_t group_tokens, int32
  * Errors: INVALID_ARG (NULL k/v, bad layer range, n_frames < 0, misaligned
  * pointer or stride), CAPACITY (T + n_frames > capacity_groups; nothing is
  * evicted), NOT_BOUND, UNSUPPORTED (more than 65535 frames or 32767 layers in one
- * call; a token stride so large that one head tile, (G + 1024) * strides[3]
+ * call, or n_frames * n_layers * H_k * (G + 1) above 2^31 - 1; a token stride so large that one head tile, (G + 1024) * strides[3]
  * elements, spans 2 GiB or more), HIP.  n_frames == 0 or n_layers == 0 is a
  * successful no-op.  first_group is written by successful calls only.
  */

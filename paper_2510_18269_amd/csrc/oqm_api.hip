@@ -200,10 +200,14 @@ tom_status_t tom_oqm_quantize_append(tom_oqm_t* h, int32_t layer0, int32_t n_lay
         return fail(TOM_ERR_INVALID_ARG, "k, v and k_for_summary must be 16-byte aligned");
     if (n_frames > 65535 || 2 * n_layers > 65535)
         return fail(TOM_ERR_UNSUPPORTED, "at most 65535 frames and 32767 layers per call");
+    // the head_dim-axis kernel takes up to G + 1 workgroups per (frame, layer, head) in a 1-D grid
+    if ((int64_t)n_frames * n_layers * c.n_kv_heads * ((int64_t)c.group_tokens + 1) > 0x7fffffffLL)
+        return fail(TOM_ERR_UNSUPPORTED, "n_frames * n_layers * n_kv_heads * (group_tokens + 1) exceeds 2^31 - 1: "
+                                         "append fewer frames per call");
     if (((int64_t)c.group_tokens + 1024) * strides[3] * eb >= (1LL << 31))
         return fail(TOM_ERR_UNSUPPORTED, "one head tile spans 2 GiB or more (token stride too large)");
 
-    QuantArgs a;
+    QuantArgs a{};
     a.k = k;
     a.v = v;
     a.ksum = k_for_summary ? k_for_summary : k;

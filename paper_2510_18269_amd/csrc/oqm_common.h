@@ -57,7 +57,16 @@ struct QuantArgs {
     int32_t qaxis;
     int32_t bits;  // 4 or 2
     int32_t meta_bf16;  // (scale, zero) stored as bfloat16 pairs
+    // Filled in by the head_dim-axis launcher: its grid decomposition and the reciprocals
+    // (floor(2^32 / d)) that let the kernel divide by these run-time constants in three
+    // instructions instead of a full integer division per workgroup and lane.
+    int32_t v_chunks;  // workgroups per V tile
+    uint32_t lanes_per_row, rows_per_pass;
+    uint32_t inv_lanes_per_row, inv_heads, inv_layers, inv_v_chunks;
 };
+
+// floor(2^32 / d) for d >= 1 (saturated for d == 1): the constant of oqm::div_by in the device header.
+inline uint32_t reciprocal_u32(uint32_t d) { return d <= 1 ? 0xffffffffu : (uint32_t)((1ull << 32) / d); }
 
 struct DequantArgs {
     const uint8_t* codes;

@@ -19,6 +19,13 @@ struct In_f32 {};
 struct In_bf16 {};
 struct In_f16 {};
 
+// n / d for n < 2^32 and a run-time constant d >= 1 whose m = floor(2^32 / d) (2^32 - 1 for
+// d == 1) came from the host: the high product is the quotient or one less.
+__device__ __forceinline__ uint32_t div_by(uint32_t n, uint32_t d, uint32_t m) {
+    const uint32_t q = __umulhi(n, m);
+    return n - q * d >= d ? q + 1u : q;
+}
+
 // ---- DPP lane exchange ----------------------------------------------------
 // dpp_ctrl encodings: quad_perm[1,0,3,2] = 0xB1 (lane ^ 1), quad_perm[2,3,0,1] = 0x4E
 // (lane ^ 2), row_half_mirror = 0x141 (lane -> 7 - lane within 8), row_mirror = 0x140

@@ -3,14 +3,31 @@
 // packing, and the summary key (mean of the un-quantized keys over the G
 // tokens of the group) in the same pass over K.
 //
-// Work decomposition.  One workgroup of 256 threads owns one
-// (frame, layer, K|V, head) tile of G x d elements; the 3-D grid is
-// (head, 2*layer + K|V, frame) so no index division is needed.  A lane owns 8
-// consecutive channels of one token row: one 128-bit load in, one 32-bit word
-// of packed nibbles out, so every load and store instruction of a wave covers
-// one contiguous span (1 KB in, 256 B out).  A quant-group of gs channels
-// lives in gs/8 adjacent lanes; its min and max are all-reduced with DPP lane
-// swaps; the first lane of the group stores its (scale, zero) pair (8 bytes).
+// Work decomposition.  A lane owns 8 consecutive channels of one token row: one
+// 128-bit load in, one 32-bit word of packed nibbles out, so every load and
+// store instruction of a wave covers one contiguous span (1 KB in, 256 B out).
+// A quant-group of gs channels lives in gs/8 adjacent lanes; its min and max are
+// all-reduced with DPP lane swaps; the first lane of the group stores its
+// (scale, zero) pair (8 bytes).
+//
+// A K tile (one (frame, layer, head) block of G x d keys) is walked by ONE
+// workgroup of 256 threads, a few token rows per trip, because the summary key
+// needs the column sums over all G rows and a reduction across workgroups costs
+// more than it saves (measured: float64 atomics or written-through partials plus an
+// arrival counter add 10 to 40 % to the kernel).  A V tile has no such coupling:
+// it is cut into chunks of one trip (32 rows at head_dim 128) and every chunk is a
+// workgroup of its own.  The 1-D grid holds all V chunks first, in the order the
+// tiles lie in memory, then all K tiles.  Measured on MI355X at 28 layers x 32
+// frames x 196 x 128 (474 MB per launch): whole tiles for K and V 100 us; V chunks
+// then K tiles 93 us; K tiles then V chunks 94 us; chunks and tiles interleaved in
+// blocks of 16 to 896 tiles 96 to 99 us (two address streams at once are slower
+// than one after the other); a role pattern with period 8 in the workgroup id
+// (e.g. one K tile after every 7 V chunks) puts all K tiles on one of the eight
+// XCDs, which take workgroups round-robin: 204 us.  Chunked workgroups stream
+// faster because the workgroups in flight then cover one dense, moving address
+// window instead of thousands of tiles at once; the same kernel with every tile
+// chunked and no summary key takes 86 us, an arithmetic-free linear stream of the
+// same byte mix 80 us.
 //
 // The kernel moves 2.64 B per element (bf16 in, gs 64).  At HBM speed that leaves
 // room for only about a dozen instructions per element on the plain fp32 vector
@@ -36,23 +53,41 @@ constexpr int kUnrollStream = 2;
 constexpr int kUnrollShallow = 13;
 constexpr int64_t kShallowTiles = 256;  // compute units of the chip
 
+// a.v_chunks: workgroups per V tile (each takes kUnroll * rows-per-pass token rows); 1 = whole tile.
 template <typename IN, int LPG, bool SEPARATE_SUMMARY, int BITS, bool MB, int kUnroll>
 __global__ void __launch_bounds__(kBlock) quantize_append_kernel(const QuantArgs a) {
     constexpr int EB = elem_bytes<IN>::value;
     constexpr uint32_t CW = BITS;  // bytes of packed codes per lane and row (8 channels)
     const int H = a.n_kv_heads, d = a.head_dim, G = a.group_tokens;
 
-    const int h = blockIdx.x;
-    const int kv = blockIdx.y & 1;
-    const int li = blockIdx.y >> 1;
-    const int f = blockIdx.z;
+    const int lpr = a.lanes_per_row;  // d / 8
+    const int rpp = a.rows_per_pass;  // token rows per pass of the workgroup: 256 / lpr
+    const int step = kUnroll * rpp;   // token rows per trip
+    const int v_chunks = a.v_chunks;
+
+    // Workgroup id -> role.  [0, items * v_chunks): chunk (id % v_chunks) of the V tile of item
+    // id / v_chunks; after those: the K tile of item id - items * v_chunks.  Items run over
+    // (frame, layer, head), head fastest, which is the order of a contiguous input tensor.
+    const int items = a.n_frames * a.n_layers * H;
+    int item = blockIdx.x, kv = 1, row_begin = 0, row_end = G;
+    if (item >= items * v_chunks) {
+        kv = 0;
+        item -= items * v_chunks;
+    } else if (v_chunks > 1) {
+        const int tile_item = div_by(item, v_chunks, a.inv_v_chunks);
+        row_begin = (item - tile_item * v_chunks) * step;
+        row_end = min(G, row_begin + step);
+        item = tile_item;
+    }
+    const int fl = div_by(item, H, a.inv_heads);
+    const int h = item - fl * H;
+    const int f = div_by(fl, a.n_layers, a.inv_layers);
+    const int li = fl - f * a.n_layers;
     const int l = a.layer0 + li;
     const int64_t t = (int64_t)a.first_group + f;
 
-    const int lpr = d >> 3;         // lanes per token row
-    const int rpp = kBlock / lpr;   // token rows per pass of the workgroup
     const int tid = threadIdx.x;
-    const int row0 = tid / lpr;
+    const int row0 = div_by(tid, lpr, a.inv_lanes_per_row);
     const int slot = tid - row0 * lpr;
     const bool active = row0 < rpp;
     const int ng = lpr / LPG;       // quant-groups per token row
@@ -131,8 +166,7 @@ __global__ void __launch_bounds__(kBlock) quantize_append_kernel(const QuantArgs
     Raw8<IN> buf[kUnroll];
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) zero_raw(buf[u]);  // defined contents for rows never loaded
-    const int step = kUnroll * rpp;
-    for (int r0 = 0; r0 < G; r0 += step) {
+    for (int r0 = row_begin; r0 < row_end; r0 += step) {
         if (r0 + wave_row0 >= G) break;  // nothing left for this wave (uniform)
         fetch(buf, r0);
         process(buf, r0);
@@ -169,9 +203,23 @@ __global__ void __launch_bounds__(kBlock) quantize_append_kernel(const QuantArgs
 }
 
 template <typename IN, int LPG, int BITS, bool MB>
-hipError_t launch_b(const QuantArgs& a, hipStream_t s) {
-    const dim3 grid(a.n_kv_heads, 2 * a.n_layers, a.n_frames);
-    const bool shallow = (int64_t)grid.x * grid.y * grid.z <= kShallowTiles;
+hipError_t launch_b(const QuantArgs& args, hipStream_t s) {
+    QuantArgs a = args;
+    const int64_t items = (int64_t)a.n_kv_heads * a.n_layers * a.n_frames;
+    const bool shallow = 2 * items <= kShallowTiles && a.ksum == a.k;
+    // V tiles: one workgroup per trip of the streaming form; whole tiles in the shallow form
+    const int rows_per_trip = kUnrollStream * (kBlock / (a.head_dim / 8));
+    const int v_chunks = shallow ? 1 : (a.group_tokens + rows_per_trip - 1) / rows_per_trip;
+    const int64_t blocks = items * (v_chunks + 1);
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;  // the API layer has refused this already
+    a.v_chunks = v_chunks;
+    a.lanes_per_row = (uint32_t)a.head_dim / 8u;
+    a.rows_per_pass = (uint32_t)kBlock / a.lanes_per_row;
+    a.inv_lanes_per_row = reciprocal_u32(a.lanes_per_row);
+    a.inv_heads = reciprocal_u32((uint32_t)a.n_kv_heads);
+    a.inv_layers = reciprocal_u32((uint32_t)a.n_layers);
+    a.inv_v_chunks = reciprocal_u32((uint32_t)v_chunks);
+    const dim3 grid((unsigned)blocks);
     if (a.ksum != a.k)
         quantize_append_kernel<IN, LPG, true, BITS, MB, kUnrollStream><<<grid, dim3(kBlock), 0, s>>>(a);
     else if (shallow)
