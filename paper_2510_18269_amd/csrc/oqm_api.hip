@@ -58,6 +58,12 @@ static tom_status_t check_config(const tom_oqm_config_t* c) {
     }
     if ((int64_t)c->n_kv_heads * c->head_dim > 8192)
         return fail(TOM_ERR_UNSUPPORTED, "n_kv_heads * head_dim > 8192 is not covered by the score kernels");
+    // every storage array must have a byte size (and element offsets) that 64-bit arithmetic holds;
+    // input elements (4 bytes at most) bound codes, metadata and keys alike
+    const unsigned __int128 elems = (unsigned __int128)c->n_layers * 2 * (unsigned)c->capacity_groups *
+                                    (unsigned)c->n_kv_heads * (unsigned)c->group_tokens * (unsigned)c->head_dim;
+    if (elems * 8 >= ((unsigned __int128)1 << 62))
+        return fail(TOM_ERR_UNSUPPORTED, "the storage arrays of this configuration would exceed 2^62 bytes");
     return TOM_OK;
 }
 
@@ -168,7 +174,7 @@ void tom_oqm_destroy(tom_oqm_t* h) { delete h; }
 
 int32_t tom_oqm_k_from_budget(int64_t budget_tokens, int32_t group_tokens, int32_t stored_groups) {
     if (budget_tokens < 0 || group_tokens < 1 || stored_groups < 0) return 0;
-    const int64_t a = (budget_tokens + group_tokens - 1) / group_tokens;
+    const int64_t a = budget_tokens / group_tokens + (budget_tokens % group_tokens != 0);  // ceil, no overflow
     return (int32_t)(a < stored_groups ? a : stored_groups);
 }
 
@@ -190,10 +196,12 @@ tom_status_t tom_oqm_quantize_append(tom_oqm_t* h, int32_t layer0, int32_t n_lay
     if (!k || !v || !strides) return fail(TOM_ERR_INVALID_ARG, "k, v and strides must be non-NULL");
     const tom_oqm_config_t& c = h->cfg;
     const int eb = dtype_bytes(c.in_dtype);
+    constexpr int64_t kMaxStride = int64_t{1} << 40;  // elements; far beyond any device tensor
     for (int i = 0; i < 4; ++i)
-        if (strides[i] < 0 || (strides[i] * eb) % 16)
-            return fail(TOM_ERR_INVALID_ARG, "strides[%d] = %lld must be >= 0 and a multiple of 16 bytes",
-                        i, (long long)strides[i]);
+        if (strides[i] < 0 || strides[i] > kMaxStride || (strides[i] * eb) % 16)
+            return fail(TOM_ERR_INVALID_ARG,
+                        "strides[%d] = %lld must be in [0, 2^40] elements and a multiple of 16 bytes", i,
+                        (long long)strides[i]);
     if (strides[3] < c.head_dim && c.group_tokens > 1)
         return fail(TOM_ERR_INVALID_ARG, "token stride %lld is smaller than head_dim", (long long)strides[3]);
     if (!aligned16(k) || !aligned16(v) || !aligned16(k_for_summary))
@@ -201,10 +209,11 @@ tom_status_t tom_oqm_quantize_append(tom_oqm_t* h, int32_t layer0, int32_t n_lay
     if (n_frames > 65535 || 2 * n_layers > 65535)
         return fail(TOM_ERR_UNSUPPORTED, "at most 65535 frames and 32767 layers per call");
     // the head_dim-axis kernel takes up to G + 1 workgroups per (frame, layer, head) in a 1-D grid
-    if ((int64_t)n_frames * n_layers * c.n_kv_heads * ((int64_t)c.group_tokens + 1) > 0x7fffffffLL)
+    // (n_frames <= 65535 and n_layers * n_kv_heads < 2^25, so the first product fits 64 bits)
+    if ((int64_t)n_frames * n_layers * c.n_kv_heads > 0x7fffffffLL / ((int64_t)c.group_tokens + 1))
         return fail(TOM_ERR_UNSUPPORTED, "n_frames * n_layers * n_kv_heads * (group_tokens + 1) exceeds 2^31 - 1: "
                                          "append fewer frames per call");
-    if (((int64_t)c.group_tokens + 1024) * strides[3] * eb >= (1LL << 31))
+    if (strides[3] > ((1LL << 31) - 1) / eb / ((int64_t)c.group_tokens + 1024))
         return fail(TOM_ERR_UNSUPPORTED, "one head tile spans 2 GiB or more (token stride too large)");
 
     QuantArgs a{};
