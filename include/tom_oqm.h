@@ -250,8 +250,9 @@ tom_status_t tom_oqm_topk(const float* scores_device, int64_t score_stride, int3
  *                 aligned.  Rows >= k_eff * G are never written: the active
  *                 buffer is bounded by k * G tokens per layer whatever T is.
  * An index outside [0, T) is skipped by the kernel (its rows stay untouched).
- * Errors: INVALID_ARG, NOT_BOUND, UNSUPPORTED (more than 65535 layers per call
- * or more than 32767 KV heads), HIP.  k_eff == 0 is a no-op.
+ * Errors: INVALID_ARG, NOT_BOUND, UNSUPPORTED (more than 65535 layers per call,
+ * more than 32767 KV heads, or k_eff * ceil(G / 3) above 2^31 - 1), HIP.
+ * k_eff == 0 is a no-op.
  */
 tom_status_t tom_oqm_dequant_gather(const tom_oqm_t* h, int32_t layer0, int32_t n_layers,
                                     const int32_t* idx_device, int32_t k, int32_t k_eff,

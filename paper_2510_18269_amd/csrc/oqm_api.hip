@@ -383,6 +383,9 @@ static tom_status_t assemble_impl(const tom_oqm_t* h, int32_t layer0, int32_t n_
     const tom_oqm_config_t& c = h->cfg;
     if (2 * c.n_kv_heads > 65535 || n_layers > 65535)
         return fail(TOM_ERR_UNSUPPORTED, "at most 32767 KV heads and 65535 layers per call");
+    // the gather takes up to ceil(G / 3) workgroups per selected tile along one grid dimension
+    if ((int64_t)k_eff * (((int64_t)c.group_tokens + 2) / 3) > 0x7fffffffLL)
+        return fail(TOM_ERR_UNSUPPORTED, "k_eff * group_tokens / 3 exceeds 2^31 - 1");
     if (copy_prefix) {  // grid of the prefix copy: (16-byte chunks / 256, H_k * n_layers, 2)
         const int64_t prefix_bytes = (int64_t)prefix_rows * c.head_dim * dtype_bytes(c.out_dtype);
         if ((int64_t)c.n_kv_heads * n_layers > 65535)
@@ -392,7 +395,7 @@ static tom_status_t assemble_impl(const tom_oqm_t* h, int32_t layer0, int32_t n_
             return fail(TOM_ERR_UNSUPPORTED, "prefix copy: prefix_rows * head_dim is too large");
     }
     if (!launch) return TOM_OK;
-    DequantArgs a;
+    DequantArgs a{};
     a.codes = h->codes;
     a.meta = h->meta;
     a.idx = idx;

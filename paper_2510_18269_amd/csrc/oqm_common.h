@@ -80,6 +80,10 @@ struct DequantArgs {
     int32_t bits;         // 4 or 2
     int32_t meta_bf16;    // (scale, zero) stored as bfloat16 pairs
     int32_t prefix_rows;  // rows of each head's active buffer that precede the gathered groups
+    // Filled in by the launcher: workgroups per tile, the token rows each takes, and the
+    // reciprocal floor(2^32 / chunks) for oqm::div_by.
+    int32_t chunks, rows_per_chunk;
+    uint32_t inv_chunks;
 };
 
 struct ScoreArgs {

@@ -1,15 +1,23 @@
 // Reconstruction of the selected frame-groups into the bounded active KV buffer
 // (paper Sec. 3.4, Eq. 11 and Eq. 13; supplement "Cache reconstruction for decoding").
 //
-// Grid (rank, 2*head + K|V, layer): one workgroup of 256 threads owns one head
-// tile of one selected group; consecutive workgroups write consecutive row blocks
-// of the active buffer.  It reads the group index from device memory (the
-// index array never visits the host), streams the tile's packed nibbles and
-// (scale, zero) pairs, and writes G x d outputs to token rows
-// [rank*G, (rank+1)*G) of the layer's active buffer.  A lane turns one 32-bit
-// word of codes (8 channels) into one 128-bit non-temporal store, so each store
-// instruction of a wave writes 1 KB of contiguous bf16.  HBM-bound: 0.5 + 8/gs
-// bytes read and 2 bytes written per element.
+// Grid (rank * chunks + chunk, 2*head + K|V, layer): a workgroup of 256 threads owns
+// up to three row passes (48 token rows at head_dim 128) of one head tile of one
+// selected group; consecutive workgroups write consecutive row blocks of the active
+// buffer.  It reads the group index from device memory (the index array never visits
+// the host), streams its rows' packed nibbles and (scale, zero) pairs, and writes them
+// to token rows [rank*G, (rank+1)*G) of the layer's active buffer.  A lane turns one
+// 32-bit word of codes (8 channels) into one 128-bit non-temporal store, so each store
+// instruction of a wave writes 1 KB of contiguous bf16.  HBM-bound: 0.5 + 8/gs bytes
+// read and 2 bytes written per element.
+//
+// Rows per workgroup, measured at 28 layers x 64 groups x 196 x 128 (944 MB, random
+// groups): whole tile (13 passes, all loads first) 171 us; 7 / 6 chunks 178 / 176 us;
+// 5 chunks of 40 rows 167 us; 3 chunks of 66 rows 168 us; 2 chunks 173 us; chunks of one
+// pass 216 us.  Chunks of unequal size whose count divides 8 are slow (3 x 64 + 4 rows:
+// 193 us): workgroup ids go round-robin over the eight XCDs, so all the short chunks land
+// on the same two.  With contiguous groups instead of random ones the same kernel takes
+// 152 us: what is left to a dense stream is the DRAM row locality of 12.5 KB pieces.
 #include <type_traits>
 
 #include "oqm_common.h"
@@ -18,15 +26,17 @@
 namespace oqm {
 namespace {
 
-// kUnroll: rows per lane whose loads are issued before any is converted; the host picks it
-// so that a whole tile is covered in one trip when it fits (13 trips of 16 rows for 196 x 128).
+// kUnroll: rows per lane whose loads are issued before any is converted (the host cuts the tile
+// into chunks that one trip covers).
 template <typename OUT, int kUnroll, bool TOKEN_AXIS, int BITS, bool MB>
 __global__ void __launch_bounds__(kBlock) dequant_gather_kernel(const DequantArgs a, const int lpg) {
     constexpr int EB = elem_bytes<OUT>::value;
     constexpr uint32_t CW = BITS;          // bytes of packed codes per lane and row (8 channels)
     constexpr uint32_t CMASK = (1u << BITS) - 1u;
     const int H = a.n_kv_heads, d = a.head_dim, G = a.group_tokens;
-    const int r = blockIdx.x;
+    const int r = a.chunks > 1 ? (int)div_by(blockIdx.x, a.chunks, a.inv_chunks) : (int)blockIdx.x;
+    const int row_begin = ((int)blockIdx.x - r * a.chunks) * a.rows_per_chunk;
+    const int row_end = min(G, row_begin + a.rows_per_chunk);
     const int kv = blockIdx.y & 1;
     const int h = blockIdx.y >> 1;
     const int li = blockIdx.z;
@@ -61,7 +71,7 @@ __global__ void __launch_bounds__(kBlock) dequant_gather_kernel(const DequantArg
     const int meta_lane = TOKEN_AXIS ? 0 : row0 * ng + slot / lpg;
     const uint32_t out_lane = ((uint32_t)row0 * d + slot * 8u) * EB;
 
-    for (int r0 = 0; r0 + row0 < G; r0 += kUnroll * rpp) {
+    for (int r0 = row_begin; r0 + row0 < row_end; r0 += kUnroll * rpp) {
         uint32_t w[kUnroll];
         meta_pair sm[kUnroll];
 #pragma unroll
@@ -69,7 +79,7 @@ __global__ void __launch_bounds__(kBlock) dequant_gather_kernel(const DequantArg
             const int rb = r0 + u * rpp;
             w[u] = 0u;
             sm[u] = meta_pair{};
-            if (rb + row0 < G) {
+            if (rb + row0 < row_end) {
                 w[u] = load_codes8<BITS>(codes_t + (code_lane + (uint32_t)rb * lpr * CW));
                 if (!TOKEN_AXIS) sm[u] = meta_t[meta_lane + rb * ng];
             }
@@ -77,7 +87,7 @@ __global__ void __launch_bounds__(kBlock) dequant_gather_kernel(const DequantArg
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             const int rb = r0 + u * rpp;
-            if (rb + row0 < G) {
+            if (rb + row0 < row_end) {
                 float x[8];
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
@@ -105,11 +115,17 @@ __global__ void __launch_bounds__(kBlock) prefix_copy_kernel(const DequantArgs a
 }
 
 template <typename OUT>
-hipError_t launch_t(const DequantArgs& a, hipStream_t s) {
-    if (a.n_layers == 0 || a.k_eff == 0) return hipSuccess;
-    const dim3 grid(a.k_eff, 2 * a.n_kv_heads, a.n_layers), block(kBlock);
+hipError_t launch_t(const DequantArgs& args, hipStream_t s) {
+    if (args.n_layers == 0 || args.k_eff == 0) return hipSuccess;
+    DequantArgs a = args;
     const int rpp = kBlock / (a.head_dim / 8);
-    const int trips = (a.group_tokens + rpp - 1) / rpp;  // row passes per tile
+    const int passes = (a.group_tokens + rpp - 1) / rpp;  // row passes per tile
+    // up to four passes: one workgroup per tile; more: equal chunks of at most three passes
+    a.chunks = passes <= 4 ? 1 : (passes + 2) / 3;
+    a.rows_per_chunk = (a.group_tokens + a.chunks - 1) / a.chunks;
+    a.inv_chunks = reciprocal_u32((uint32_t)a.chunks);
+    if ((int64_t)a.k_eff * a.chunks > 0x7fffffffLL) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)(a.k_eff * a.chunks), 2 * a.n_kv_heads, a.n_layers), block(kBlock);
     const int lpg = a.qgroup / 8;  // unused for the token axis
     const bool tok = a.qaxis == TOM_QAXIS_TOKENS;
     auto go = [&](auto unroll, auto bits, auto mb) {
@@ -126,9 +142,8 @@ hipError_t launch_t(const DequantArgs& a, hipStream_t s) {
         if (a.bits == 2) with_meta(unroll, std::integral_constant<int, 2>{});
         else with_meta(unroll, std::integral_constant<int, 4>{});
     };
-    if (trips <= 4) with_bits(std::integral_constant<int, 4>{});
-    else if (trips <= 8 || trips > 13) with_bits(std::integral_constant<int, 8>{});
-    else with_bits(std::integral_constant<int, 13>{});
+    if (passes <= 4) with_bits(std::integral_constant<int, 4>{});
+    else with_bits(std::integral_constant<int, 3>{});
     return hipGetLastError();
 }
 
