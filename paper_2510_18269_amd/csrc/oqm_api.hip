@@ -295,7 +295,7 @@ static tom_status_t score_impl(const tom_oqm_t* h, int32_t layer0, int32_t n_lay
 
     const tom_oqm_config_t& c = h->cfg;
     const size_t hd = (size_t)c.n_kv_heads * c.head_dim;
-    ScoreArgs a;
+    ScoreArgs a{};
     a.keys = h->keys;
     a.q = q;
     a.scores = scores;

@@ -97,6 +97,9 @@ struct ScoreArgs {
     int64_t score_stride;
     int32_t n_kv_heads, n_q_heads, head_dim, capacity_groups;
     int32_t layer0, n_layers, t_q, n_groups, sim, q_dtype;
+    // Filled in by the launcher of the per-token contraction: its unit decomposition.
+    int32_t gemm_units, gemm_units_per_xcd, gemm_tiles_per_layer;
+    uint32_t inv_gemm_tiles_per_layer;
 };
 
 // ---- launchers (each validates nothing: the API layer has done that) ------

@@ -202,8 +202,15 @@ __global__ void __launch_bounds__(kBlock) score_mean_query_kernel(const ScoreArg
 
 // ------------------------------------------------------------------ per-token GEMM
 // S[j][t] = sum_e qtok[j][e] * key[t][e], j < T_q query tokens, t < T groups, e < H_k*d.
-// grid (ceil(T / 64), n_layers); 4 waves; wave w owns groups n0 + 16w .. + 15 and up to
-// four 16-token row tiles.  Operands are staged through LDS in chunks of kGemmK along e.
+// Unit of work = (layer, 64 consecutive groups): one workgroup of 4 waves; wave w owns groups
+// n0 + 16w .. + 15 and up to four 16-token row tiles.  Operands are staged through LDS in
+// chunks of kGemmK along e.
+//
+// Workgroup id -> unit.  Ids go round-robin over the eight XCDs, each with its own L2, so
+// XCD x is given the contiguous run of units [x * per, (x + 1) * per): it then touches the
+// folded query block (T_q x H_k*d float64, 256 KB at 64 x 512) of about n_layers / 8 + 1
+// layers instead of every layer's (with a (tile, layer) grid every XCD fetched every layer's
+// block: 118 MB of traffic for 72 MB of operands at 28 layers x 1024 groups).
 //
 // v_mfma_f64_16x16x4_f64 register layout (checked on hardware by the GPU tests through
 // the per-token score output): lane = 16*kk + i supplies A[i][kk] and B[kk][i]; lane
@@ -330,8 +337,10 @@ __global__ void __launch_bounds__(kBlock) score_token_gemm_kernel(const ScoreArg
     // two LDS stages: chunk c is multiplied while chunk c+1 travels global -> registers -> LDS
     __shared__ double As[2][kGemmM * kLdA];
     __shared__ float Bs[2][kGemmN * kLdB];
-    const int li = blockIdx.y;
-    const int n0 = blockIdx.x * kGemmN;
+    const int unit = (int)(blockIdx.x & 7u) * a.gemm_units_per_xcd + (int)(blockIdx.x >> 3);
+    if (unit >= a.gemm_units) return;  // uniform per workgroup
+    const int li = div_by(unit, a.gemm_tiles_per_layer, a.inv_gemm_tiles_per_layer);
+    const int n0 = (unit - li * a.gemm_tiles_per_layer) * kGemmN;
     const int HD = a.n_kv_heads * a.head_dim;
     const int T = a.n_groups, Tq = a.t_q;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -393,10 +402,16 @@ hipError_t launch_score_mean_query(const ScoreArgs& a, hipStream_t s) {
 }  // namespace oqm
 
 namespace oqm {
-hipError_t launch_score_token_gemm(const ScoreArgs& a, hipStream_t s) {
-    if (a.n_layers == 0 || a.n_groups == 0) return hipSuccess;
-    const dim3 grid((a.n_groups + kGemmN - 1) / kGemmN, a.n_layers);
-    score_token_gemm_kernel<<<grid, dim3(kBlock), 0, s>>>(a);
+hipError_t launch_score_token_gemm(const ScoreArgs& args, hipStream_t s) {
+    if (args.n_layers == 0 || args.n_groups == 0) return hipSuccess;
+    ScoreArgs a = args;
+    a.gemm_tiles_per_layer = (a.n_groups + kGemmN - 1) / kGemmN;
+    a.inv_gemm_tiles_per_layer = reciprocal_u32((uint32_t)a.gemm_tiles_per_layer);
+    const int64_t units = (int64_t)a.gemm_tiles_per_layer * a.n_layers;
+    if (units > 0x7fffffffLL - 8) return hipErrorInvalidValue;  // 2^25 tiles x 65535 layers at most: never
+    a.gemm_units = (int32_t)units;
+    a.gemm_units_per_xcd = (int32_t)((units + 7) / 8);
+    score_token_gemm_kernel<<<dim3(8u * (unsigned)a.gemm_units_per_xcd), dim3(kBlock), 0, s>>>(a);
     return hipGetLastError();
 }
 }  // namespace oqm
