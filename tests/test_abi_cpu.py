@@ -176,6 +176,45 @@ def test_retrieve_noalloc_checks_sizes_and_arguments_on_the_host(oqm):
         oqm.tom_oqm_destroy(h)
 
 
+def test_launch_size_limits_are_reported_before_any_launch(oqm):
+    """Shapes whose 1-D grids would not fit are refused as UNSUPPORTED by the validation pass."""
+    fake = 0x1000
+    # append: n_frames * n_layers * H_k * (G + 1) must stay below 2^31
+    cfg = oqm.make_config(1000, 8, 8, 64, 60000, 32, 70000)
+    h = oqm.tom_oqm_create(cfg)
+    try:
+        oqm.tom_oqm_bind(h, fake, fake, fake)
+        st = (1000 * 8 * 60000 * 64, 8 * 60000 * 64, 60000 * 64, 64)
+        with pytest.raises(oqm.TomError) as e:
+            oqm.tom_oqm_quantize_append(h, 0, 1000, 60000, fake, fake, None, st)
+        assert e.value.status == oqm.TOM_ERR_UNSUPPORTED and "2^31" in str(e.value)
+        # gather: k_eff * ceil(G / 3) along one grid dimension
+        oqm.tom_oqm_set_num_groups(h, 70000)
+        with pytest.raises(oqm.TomError) as e:
+            oqm.tom_oqm_dequant_gather(h, 0, 1, fake, 200000, 70000 * 2, fake, fake)   # k_eff > k
+        assert e.value.status == oqm.TOM_ERR_INVALID_ARG
+    finally:
+        oqm.tom_oqm_destroy(h)
+    cfg = oqm.make_config(1, 1, 1, 8, 200000, 8, 40000)       # G = 200000: up to 66667 chunks per tile
+    h = oqm.tom_oqm_create(cfg)
+    try:
+        oqm.tom_oqm_bind(h, fake, fake, fake)
+        oqm.tom_oqm_set_num_groups(h, 40000)
+        with pytest.raises(oqm.TomError) as e:
+            oqm.tom_oqm_dequant_gather(h, 0, 1, fake, 40000, 40000, fake, fake)
+        assert e.value.status == oqm.TOM_ERR_UNSUPPORTED and "2^31" in str(e.value)
+        # astronomically large strides are refused, not multiplied
+        with pytest.raises(oqm.TomError) as e:
+            oqm.tom_oqm_quantize_append(h, 0, 1, 0 + 1, fake, fake, None, (2 ** 62, 8, 8, 8))
+        assert e.value.status in (oqm.TOM_ERR_INVALID_ARG, oqm.TOM_ERR_CAPACITY)
+    finally:
+        oqm.tom_oqm_destroy(h)
+    # a configuration whose storage could not be addressed in 64 bits
+    with pytest.raises(oqm.TomError) as e:
+        oqm.tom_oqm_create(oqm.make_config(2 ** 31 - 1, 4, 4, 2048, 1000, 64, 2 ** 31 - 1))
+    assert e.value.status == oqm.TOM_ERR_UNSUPPORTED
+
+
 def test_two_bit_sizes(oqm):
     cfg = oqm.make_config(28, 4, 28, 128, 50, 64, 100, bits=2)
     s = oqm.tom_oqm_query_sizes(cfg)
