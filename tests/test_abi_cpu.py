@@ -191,8 +191,8 @@ def test_launch_size_limits_are_reported_before_any_launch(oqm):
         # gather: k_eff * ceil(G / 3) along one grid dimension
         oqm.tom_oqm_set_num_groups(h, 70000)
         with pytest.raises(oqm.TomError) as e:
-            oqm.tom_oqm_dequant_gather(h, 0, 1, fake, 200000, 70000 * 2, fake, fake)   # k_eff > k
-        assert e.value.status == oqm.TOM_ERR_INVALID_ARG
+            oqm.tom_oqm_dequant_gather(h, 0, 1, fake, 200000, 140000, fake, fake)   # 140000 groups x 20000 chunks
+        assert e.value.status == oqm.TOM_ERR_UNSUPPORTED and "2^31" in str(e.value)
     finally:
         oqm.tom_oqm_destroy(h)
     cfg = oqm.make_config(1, 1, 1, 8, 200000, 8, 40000)       # G = 200000: up to 66667 chunks per tile
