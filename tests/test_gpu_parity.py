@@ -76,6 +76,26 @@ def test_shapes_dtypes_and_ragged_tails(oqm, G, d, gs, dt, H_k, H_q):
     assert r["k_eff"] == 6
 
 
+@pytest.mark.parametrize("G,d,gs,H_k,frames", [
+    (65, 128, 64, 4, 20),     # 5 row passes: the gather's first chunked shape (2 x 33 rows); V tiles 32 + 32 + 1
+    (97, 128, 32, 4, 17),     # 7 passes: 3 chunks of 33 (32 + 1 rows in the last pass of each)
+    (129, 64, 16, 3, 22),     # 32 rows per pass: V chunks of 64 rows, gather 5 passes -> 2 x 65
+    (1000, 128, 64, 1, 65),   # 63 passes: 21 gather chunks of 48, 32 V chunks
+    (47, 256, 128, 2, 40),    # 8 rows per pass: 16-row V chunks, 6 passes -> 2 gather chunks of 24
+    (31, 1032, 8, 1, 65)])    # 129 lanes per row: one row per pass, 31 passes
+def test_chunk_boundaries_of_the_store_and_gather_kernels(oqm, G, d, gs, H_k, frames):
+    """The streaming form of the append cuts V tiles into one-trip chunks and the gather cuts
+    tiles of more than four row passes into equal chunks: shapes that put chunk ends next to
+    tile ends, on launches of more than 256 tiles (the streaming form) and frame by frame."""
+    w = synth_kv.Workload("X", 2, H_k, 2 * H_k, d, G, frames, gs, 5, 5, "bf16", "cosine", 4400 + G + d,
+                          "layer_std", frames)
+    assert 2 * 2 * H_k * frames > 256          # K and V tiles of 2 layers: the streaming form
+    r = _stream_and_check(oqm, w, frames)
+    assert r["k_eff"] == 5 and r["loose_rows"] == 0
+    r = _stream_and_check(oqm, w, 3, bits=2, meta="bf16")
+    assert r["k_eff"] == 5 and r["loose_rows"] == 0
+
+
 @pytest.mark.parametrize("G,d,dt,H_k,H_q", [
     (50, 128, "f16", 4, 28),           # the paper's setting: 50-token groups, FP16, per-channel scale
     (196, 128, "bf16", 4, 28), (1, 64, "f32", 1, 1), (13, 96, "bf16", 3, 6), (300, 64, "f16", 2, 2),
