@@ -1,7 +1,7 @@
-// Store step of Online Quantized Memory on gfx950: 4-bit quantization of one
-// frame-group tile per workgroup (paper Sec. 3.4, Eq. 8 and Eq. 9), nibble
-// packing, and the summary key (mean of the un-quantized keys over the G
-// tokens of the group) in the same pass over K.
+// Store step of Online Quantized Memory on gfx950: 4-bit (or 2-bit) quantization
+// of the frame-group tiles of K and V (paper Sec. 3.4, Eq. 8 and Eq. 9), code
+// packing, and the summary key (mean of the un-quantized keys over the G tokens
+// of the group) in the same pass over K.
 //
 // Work decomposition.  A lane owns 8 consecutive channels of one token row: one
 // 128-bit load in, one 32-bit word of packed nibbles out, so every load and
