@@ -211,7 +211,9 @@ hipError_t launch_t(const QuantArgs& a, hipStream_t s) {
     const int trips = (a.group_tokens + rpp - 1) / rpp;  // rows per lane
     if (trips <= 4) return launch_h<IN, 4>(a, s);
     if (trips <= 8) return launch_h<IN, 8>(a, s);
-    if (trips <= 13 && sizeof(Raw8<IN>) <= 16) return launch_h<IN, 13>(a, s);
+    if constexpr (sizeof(Raw8<IN>) <= 16) {  // 13 float32 rows would not fit the register budget
+        if (trips <= 13) return launch_h<IN, 13>(a, s);
+    }
     return launch_h<IN, 0>(a, s);
 }
 
