@@ -61,6 +61,7 @@ struct QuantArgs {
     // (floor(2^32 / d)) that let the kernel divide by these run-time constants in three
     // instructions instead of a full integer division per workgroup and lane.
     int32_t v_chunks;  // workgroups per V tile
+    int32_t v_rows_per_chunk;  // token rows each of them takes
     uint32_t lanes_per_row, rows_per_pass;
     uint32_t inv_lanes_per_row, inv_heads, inv_layers, inv_v_chunks;
 };

@@ -75,8 +75,8 @@ __global__ void __launch_bounds__(kBlock) quantize_append_kernel(const QuantArgs
         item -= items * v_chunks;
     } else if (v_chunks > 1) {
         const int tile_item = div_by(item, v_chunks, a.inv_v_chunks);
-        row_begin = (item - tile_item * v_chunks) * step;
-        row_end = min(G, row_begin + step);
+        row_begin = (item - tile_item * v_chunks) * a.v_rows_per_chunk;
+        row_end = min(G, row_begin + a.v_rows_per_chunk);
         item = tile_item;
     }
     const int fl = div_by(item, H, a.inv_heads);
@@ -118,7 +118,7 @@ __global__ void __launch_bounds__(kBlock) quantize_append_kernel(const QuantArgs
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             const int rb = r0 + u * rpp;
-            if (active && rb + row0 < G)
+            if (active && rb + row0 < row_end)
                 load_raw(src + (in_lane + (uint32_t)rb * in_row_bytes), dst[u]);
         }
     };
@@ -126,8 +126,8 @@ __global__ void __launch_bounds__(kBlock) quantize_append_kernel(const QuantArgs
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             const int rb = r0 + u * rpp;
-            if (rb + wave_row0 >= G) break;  // nothing left for this wave (uniform)
-            const bool ok = active && rb + row0 < G;
+            if (rb + wave_row0 >= row_end) break;  // nothing left for this wave (uniform)
+            const bool ok = active && rb + row0 < row_end;
             float x[8];
             widen(buf[u], x);  // lanes past the tile compute on stale rows; their results are dropped
             // Eq. 9: m = min, s = (max - min) / 15 over the quant-group.  All lanes of a
@@ -167,7 +167,7 @@ __global__ void __launch_bounds__(kBlock) quantize_append_kernel(const QuantArgs
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) zero_raw(buf[u]);  // defined contents for rows never loaded
     for (int r0 = row_begin; r0 < row_end; r0 += step) {
-        if (r0 + wave_row0 >= G) break;  // nothing left for this wave (uniform)
+        if (r0 + wave_row0 >= row_end) break;  // nothing left for this wave (uniform)
         fetch(buf, r0);
         process(buf, r0);
     }
@@ -213,6 +213,7 @@ hipError_t launch_b(const QuantArgs& args, hipStream_t s) {
     const int64_t blocks = items * (v_chunks + 1);
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;  // the API layer has refused this already
     a.v_chunks = v_chunks;
+    a.v_rows_per_chunk = (a.group_tokens + v_chunks - 1) / v_chunks;  // equal chunks, each within one trip
     a.lanes_per_row = (uint32_t)a.head_dim / 8u;
     a.rows_per_pass = (uint32_t)kBlock / a.lanes_per_row;
     a.inv_lanes_per_row = reciprocal_u32(a.lanes_per_row);
