@@ -15,8 +15,9 @@
 // needs the column sums over all G rows and a reduction across workgroups costs
 // more than it saves (measured: float64 atomics or written-through partials plus an
 // arrival counter add 10 to 40 % to the kernel).  A V tile has no such coupling:
-// it is cut into chunks of one trip (32 rows at head_dim 128) and every chunk is a
-// workgroup of its own.  The 1-D grid holds all V chunks first, in the order the
+// it is cut into equal chunks of at most one trip (7 x 28 rows at 196 x 128) and
+// every chunk is a workgroup of its own (two rows per lane in flight; one row per
+// lane is 40 % slower, three to five rows 5 % slower).  The 1-D grid holds all V chunks first, in the order the
 // tiles lie in memory, then all K tiles.  Measured on MI355X at 28 layers x 32
 // frames x 196 x 128 (474 MB per launch): whole tiles for K and V 100 us; V chunks
 // then K tiles 93 us; K tiles then V chunks 94 us; chunks and tiles interleaved in
@@ -42,20 +43,26 @@
 namespace oqm {
 namespace {
 
-// Token rows per lane and loop trip.  Two keep the register footprint small, which is what a
-// launch of many tiles wants (more resident workgroups).  A launch with at most one tile per
-// compute unit (one frame of a live stream: 224 tiles at 28 layers x 4 heads) is bound by the
-// dependent memory round trips of that one workgroup instead, so it takes all rows of a lane
-// at once (13 at 196 x 128: one trip).  Measured kernel time at 224 tiles: 8.3 against 9.8 us;
-// from two tiles per compute unit on, the two-row form is the faster one (11.3 against 11.8 us
-// at 448 tiles, 15.9 against 18.5 us at 896).
+// Two forms of the kernel.
+// Streaming (more than kShallowTiles tiles): 256 threads, two token rows per lane and trip.  The
+// small register footprint keeps eight workgroups on a compute unit, and V tiles are cut into
+// one-trip chunks (see above).
+// Shallow (a launch of at most three tiles per compute unit, e.g. one frame of a live stream:
+// 224 tiles at 28 layers x 4 heads): such a launch is bound by the dependent memory round trips
+// and the serial arithmetic of the one workgroup that owns a tile, not by bandwidth, so a tile
+// gets 1024 threads with four rows per lane in flight (the whole 196 x 128 tile in one trip).
+// Measured kernel time, shallow against streaming form: 224 tiles 6.4 / 9.8 us (7.7 us with 256
+// threads and 13 rows per lane), 448 tiles 9.6 / 11.3 us, 672 tiles 13.6 / 15.2 us, 896 tiles
+// 17.1 / 17.5 us, 1344 tiles 23.6 / 21.6 us.
 constexpr int kUnrollStream = 2;
-constexpr int kUnrollShallow = 13;
-constexpr int64_t kShallowTiles = 256;  // compute units of the chip
+constexpr int kUnrollShallow = 4;
+constexpr int kShallowThreads = 1024;
+constexpr int64_t kShallowTiles = 768;  // three per compute unit
 
-// a.v_chunks: workgroups per V tile (each takes kUnroll * rows-per-pass token rows); 1 = whole tile.
-template <typename IN, int LPG, bool SEPARATE_SUMMARY, int BITS, bool MB, int kUnroll>
-__global__ void __launch_bounds__(kBlock) quantize_append_kernel(const QuantArgs a) {
+// a.v_chunks: workgroups per V tile, a.v_rows_per_chunk token rows each (at most one trip of
+// kUnroll * rows-per-pass rows); 1 = whole tile.
+template <typename IN, int LPG, bool SEPARATE_SUMMARY, int BITS, bool MB, int kUnroll, int NT>
+__global__ void __launch_bounds__(NT) quantize_append_kernel(const QuantArgs a) {
     constexpr int EB = elem_bytes<IN>::value;
     constexpr uint32_t CW = BITS;  // bytes of packed codes per lane and row (8 channels)
     const int H = a.n_kv_heads, d = a.head_dim, G = a.group_tokens;
@@ -107,7 +114,7 @@ __global__ void __launch_bounds__(kBlock) quantize_append_kernel(const QuantArgs
     const int meta_lane = row0 * ng + slot / LPG;
     const bool meta_writer = (slot & (LPG - 1)) == 0;
 
-    __shared__ double shared_buf[kBlock * 8];  // 16 KB, key reduction
+    __shared__ double shared_buf[NT * 8];  // 16 KB at 256 threads, key reduction
 
     const bool do_sum = (kv == 0);
     double acc[8];
@@ -195,7 +202,7 @@ __global__ void __launch_bounds__(kBlock) quantize_append_kernel(const QuantArgs
     float* key = a.keys + (((int64_t)l * a.capacity_groups + t) * H + h) * d;
     // position q = i * lpr + slot holds channel slot * 8 + i: the lanes of a wave write
     // consecutive doubles (channel order would put them 64 bytes apart: 16-way bank conflicts)
-    for (int q = tid; q < d; q += kBlock) {
+    for (int q = tid; q < d; q += NT) {
         double sum = 0.0;
         for (int r = 0; r < rpp; ++r) sum += shared_buf[r * d + q];
         key[(q % lpr) * 8 + q / lpr] = (float)(sum / (double)G);
@@ -215,18 +222,20 @@ hipError_t launch_b(const QuantArgs& args, hipStream_t s) {
     a.v_chunks = v_chunks;
     a.v_rows_per_chunk = (a.group_tokens + v_chunks - 1) / v_chunks;  // equal chunks, each within one trip
     a.lanes_per_row = (uint32_t)a.head_dim / 8u;
-    a.rows_per_pass = (uint32_t)kBlock / a.lanes_per_row;
+    const int threads = shallow ? kShallowThreads : kBlock;
+    a.rows_per_pass = (uint32_t)threads / a.lanes_per_row;
     a.inv_lanes_per_row = reciprocal_u32(a.lanes_per_row);
     a.inv_heads = reciprocal_u32((uint32_t)a.n_kv_heads);
     a.inv_layers = reciprocal_u32((uint32_t)a.n_layers);
     a.inv_v_chunks = reciprocal_u32((uint32_t)v_chunks);
     const dim3 grid((unsigned)blocks);
     if (a.ksum != a.k)
-        quantize_append_kernel<IN, LPG, true, BITS, MB, kUnrollStream><<<grid, dim3(kBlock), 0, s>>>(a);
+        quantize_append_kernel<IN, LPG, true, BITS, MB, kUnrollStream, kBlock><<<grid, dim3(kBlock), 0, s>>>(a);
     else if (shallow)
-        quantize_append_kernel<IN, LPG, false, BITS, MB, kUnrollShallow><<<grid, dim3(kBlock), 0, s>>>(a);
+        quantize_append_kernel<IN, LPG, false, BITS, MB, kUnrollShallow, kShallowThreads>
+            <<<grid, dim3(kShallowThreads), 0, s>>>(a);
     else
-        quantize_append_kernel<IN, LPG, false, BITS, MB, kUnrollStream><<<grid, dim3(kBlock), 0, s>>>(a);
+        quantize_append_kernel<IN, LPG, false, BITS, MB, kUnrollStream, kBlock><<<grid, dim3(kBlock), 0, s>>>(a);
     return hipGetLastError();
 }
 

@@ -77,19 +77,19 @@ def test_shapes_dtypes_and_ragged_tails(oqm, G, d, gs, dt, H_k, H_q):
 
 
 @pytest.mark.parametrize("G,d,gs,H_k,frames", [
-    (65, 128, 64, 4, 20),     # 5 row passes: the gather's first chunked shape (2 x 33 rows); V tiles 32 + 32 + 1
-    (97, 128, 32, 4, 17),     # 7 passes: 3 chunks of 33 (32 + 1 rows in the last pass of each)
-    (129, 64, 16, 3, 22),     # 32 rows per pass: V chunks of 64 rows, gather 5 passes -> 2 x 65
-    (1000, 128, 64, 1, 65),   # 63 passes: 21 gather chunks of 48, 32 V chunks
-    (47, 256, 128, 2, 40),    # 8 rows per pass: 16-row V chunks, 6 passes -> 2 gather chunks of 24
-    (31, 1032, 8, 1, 65)])    # 129 lanes per row: one row per pass, 31 passes
+    (65, 128, 64, 4, 49),     # 5 row passes: the gather's first chunked shape (2 x 33 rows); V tiles 3 x 22
+    (97, 128, 32, 4, 49),     # 7 passes: 3 gather chunks of 33; V tiles 3 x 32 + 1 -> 4 chunks of 25
+    (129, 64, 16, 3, 65),     # 32 rows per pass: V chunks of 43 rows, gather 5 passes -> 2 x 65
+    (520, 128, 64, 4, 49),    # 33 passes: 11 gather chunks of 48, 17 V chunks of 31
+    (47, 256, 128, 2, 97),    # 8 rows per pass: 16-row V chunks, 6 passes -> 2 gather chunks of 24
+    (31, 1032, 8, 1, 193)])   # 129 lanes per row: one row per pass, 31 passes
 def test_chunk_boundaries_of_the_store_and_gather_kernels(oqm, G, d, gs, H_k, frames):
     """The streaming form of the append cuts V tiles into one-trip chunks and the gather cuts
     tiles of more than four row passes into equal chunks: shapes that put chunk ends next to
-    tile ends, on launches of more than 256 tiles (the streaming form) and frame by frame."""
+    tile ends, on launches of more than 768 tiles (the streaming form) and three frames at a time."""
     w = synth_kv.Workload("X", 2, H_k, 2 * H_k, d, G, frames, gs, 5, 5, "bf16", "cosine", 4400 + G + d,
                           "layer_std", frames)
-    assert 2 * 2 * H_k * frames > 256          # K and V tiles of 2 layers: the streaming form
+    assert 2 * 2 * H_k * frames > 768          # K and V tiles of 2 layers: the streaming form
     r = _stream_and_check(oqm, w, frames)
     assert r["k_eff"] == 5 and r["loose_rows"] == 0
     r = _stream_and_check(oqm, w, 3, bits=2, meta="bf16")
@@ -161,16 +161,17 @@ def test_bf16_metadata(oqm, qaxis, bits, G, d, gs, dt, H_k, H_q):
 
 
 @pytest.mark.parametrize("bits,meta,dt,G,d,gs,H_k,frames", [
-    (4, "f32", "bf16", 50, 128, 64, 4, 20), (2, "f32", "f16", 13, 96, 8, 3, 24),
-    (4, "bf16", "f32", 33, 256, 128, 2, 40), (2, "bf16", "bf16", 196, 128, 64, 4, 17)])
-def test_append_launches_above_and_below_one_tile_per_cu(oqm, bits, meta, dt, G, d, gs, H_k, frames):
-    """The head_dim-axis append has two forms of one kernel: all rows of a lane in flight for
-    launches of at most 256 tiles, two rows per trip above.  Most cases in this file are small
-    launches; here one call stores more than 256 tiles, then the same stream goes in frame by
-    frame, and both must match the oracle."""
+    (4, "f32", "bf16", 50, 128, 64, 4, 49), (2, "f32", "f16", 13, 96, 8, 3, 65),
+    (4, "bf16", "f32", 33, 256, 128, 2, 97), (2, "bf16", "bf16", 196, 128, 64, 4, 49)])
+def test_append_launches_above_and_below_three_tiles_per_cu(oqm, bits, meta, dt, G, d, gs, H_k, frames):
+    """The head_dim-axis append has two forms of one kernel: 1024 threads per tile with four rows
+    per lane in flight for launches of at most 768 tiles, above that 256 threads, two rows per
+    trip and V tiles cut into chunks.  Most cases in this file are small launches; here one
+    call stores more than 768 tiles, then the same stream goes in frame by frame, and both must
+    match the oracle."""
     w = synth_kv.Workload("X", 2, H_k, 2 * H_k, d, G, frames, gs, 5, 6, dt, "cosine", 2100 + G + d + bits,
                           "layer_std", frames)
-    assert H_k * 2 * 2 * frames > 256
+    assert H_k * 2 * 2 * frames > 768
     r = _stream_and_check(oqm, w, frames, bits=bits, meta=meta)
     assert r["k_eff"] == 6 and r["loose_rows"] == 0
     r = _stream_and_check(oqm, w, 1, bits=bits, meta=meta)

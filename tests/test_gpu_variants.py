@@ -46,8 +46,8 @@ def _run(oqm, *, qaxis, dt, gs, sep, bits, meta, G, frames, heads, seed):
 
 
 # head_dim axis: input type x lanes per quant-group x summary source x code width x metadata kind
-# x launch form (at most 256 tiles: all rows of a lane in flight; more: two rows per trip, V tiles
-# cut into one-trip chunks).  The group size cycles through 16 / 100 / 180 tokens = 1 / 7 / 12 row
+# x launch form (at most 768 tiles: 1024 threads per tile, four rows of a lane in flight; more:
+# 256 threads, two rows per trip, V tiles cut into chunks).  The group size cycles through 16 / 100 / 180 tokens = 1 / 7 / 12 row
 # passes: the gather's two forms (whole tile up to four passes, else chunks of at most three).
 _HD = list(itertools.product(("bf16", "f16", "f32"), (8, 16, 32, 64, 128), (False, True), (4, 2),
                              ("f32", "bf16")))
@@ -61,9 +61,9 @@ def test_every_form_of_the_head_dim_axis_kernels(oqm, dt):
             continue
         G = (16, 100, 180)[i % 3]
         _run(oqm, qaxis=0, dt=dt, gs=gs, sep=sep, bits=bits, meta=meta, G=G, frames=3, heads=2, seed=5000 + i)
-        # 65 frames x 2 heads x (K, V) = 260 tiles: the streaming form of the same kernel
-        # (40 token rows: a V tile is two chunks, 32 rows and 8)
-        _run(oqm, qaxis=0, dt=dt, gs=gs, sep=sep, bits=bits, meta=meta, G=40, frames=65, heads=2, seed=6000 + i)
+        # 195 frames x 2 heads x (K, V) = 780 tiles: the streaming form of the same kernel
+        # (40 token rows: a V tile is two chunks of 20)
+        _run(oqm, qaxis=0, dt=dt, gs=gs, sep=sep, bits=bits, meta=meta, G=40, frames=195, heads=2, seed=6000 + i)
         n += 2
     assert n == 80
 
