@@ -188,7 +188,7 @@ tom_status_t tom_oqm_quantize_append(tom_oqm_t* h, int32_t layer0, int32_t n_lay
                                      void* hip_stream, int32_t* first_group);
 
 /* Bytes of device workspace tom_oqm_score_groups needs for this call shape
- * (0 on invalid arguments).  `path` is a tom_score_path_t. */
+ * (0 on arguments that call would refuse).  `path` is a tom_score_path_t. */
 size_t tom_oqm_score_workspace_bytes(const tom_oqm_t* h, int32_t n_layers, int32_t t_q,
                                      int32_t path, int32_t want_token_scores);
 
@@ -210,8 +210,8 @@ size_t tom_oqm_score_workspace_bytes(const tom_oqm_t* h, int32_t n_layers, int32
  *   workspace     device, 16-byte aligned, at least
  *                 tom_oqm_score_workspace_bytes(...) bytes; scratch, contents
  *                 undefined afterwards; concurrent calls need separate ones.
- * Errors: INVALID_ARG, NOT_BOUND, UNSUPPORTED (more than 65535 layers per call),
- * HIP.  T == 0 is a no-op.
+ * Errors: INVALID_ARG, NOT_BOUND, UNSUPPORTED (more than 65535 layers or more than
+ * 2^20 query tokens per call), HIP.  T == 0 is a no-op.
  */
 tom_status_t tom_oqm_score_groups(const tom_oqm_t* h, int32_t layer0, int32_t n_layers,
                                   const void* q_device, int32_t q_dtype, int32_t t_q,

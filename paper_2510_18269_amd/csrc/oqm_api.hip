@@ -74,8 +74,8 @@ static void drop_stale_hip_error() { (void)hipGetLastError(); }
 
 static tom_status_t check_layers(const tom_oqm_t* h, int32_t layer0, int32_t n_layers) {
     if (layer0 < 0 || n_layers < 0 || (int64_t)layer0 + n_layers > h->cfg.n_layers)
-        return fail(TOM_ERR_INVALID_ARG, "layer range [%d, %d) is outside [0, %d)", layer0,
-                    layer0 + n_layers, h->cfg.n_layers);
+        return fail(TOM_ERR_INVALID_ARG, "layer range [%d, %lld) is outside [0, %d)", layer0,
+                    (long long)layer0 + n_layers, h->cfg.n_layers);
     return TOM_OK;
 }
 
@@ -247,6 +247,10 @@ tom_status_t tom_oqm_quantize_append(tom_oqm_t* h, int32_t layer0, int32_t n_lay
     return TOM_OK;
 }
 
+// Query tokens per call: keeps every workspace size and element offset of the score step far
+// inside 64 bits (65535 layers x 2^20 tokens x 8192 channels x 8 bytes < 2^63).
+constexpr int32_t kMaxQueryTokens = 1 << 20;
+
 static int resolve_path(int32_t path, bool want_tokens) {
     if (path == TOM_SCORE_AUTO) return want_tokens ? TOM_SCORE_TOKEN_GEMM : TOM_SCORE_MEAN_QUERY;
     return path;
@@ -254,7 +258,7 @@ static int resolve_path(int32_t path, bool want_tokens) {
 
 size_t tom_oqm_score_workspace_bytes(const tom_oqm_t* h, int32_t n_layers, int32_t t_q,
                                      int32_t path, int32_t want_token_scores) {
-    if (!h || n_layers < 0 || t_q < 1) return 0;
+    if (!h || n_layers < 0 || n_layers > h->cfg.n_layers || t_q < 1 || t_q > kMaxQueryTokens) return 0;
     const size_t hd = (size_t)h->cfg.n_kv_heads * h->cfg.head_dim;
     size_t doubles = (size_t)n_layers * hd + (size_t)n_layers * h->cfg.n_kv_heads;
     doubles = (doubles + 1) & ~(size_t)1;
@@ -274,6 +278,8 @@ static tom_status_t score_impl(const tom_oqm_t* h, int32_t layer0, int32_t n_lay
     if (!h->bound) return fail(TOM_ERR_NOT_BOUND, "tom_oqm_bind has not been called");
     if (tom_status_t st = check_layers(h, layer0, n_layers)) return st;
     if (t_q < 1) return fail(TOM_ERR_INVALID_ARG, "t_q must be >= 1");
+    if (t_q > kMaxQueryTokens)
+        return fail(TOM_ERR_UNSUPPORTED, "t_q = %d: at most %d query tokens per call", t_q, kMaxQueryTokens);
     if (!dtype_ok(q_dtype)) return fail(TOM_ERR_INVALID_ARG, "q_dtype is not a tom_dtype_t");
     if (path != TOM_SCORE_AUTO && path != TOM_SCORE_MEAN_QUERY && path != TOM_SCORE_TOKEN_GEMM)
         return fail(TOM_ERR_INVALID_ARG, "path is not a tom_score_path_t");
@@ -486,8 +492,8 @@ tom_status_t tom_oqm_retrieve_noalloc(const tom_oqm_t* h, int32_t layer0, int32_
     if (!h) return fail(TOM_ERR_INVALID_ARG, "handle is NULL");
     // Size check and full validation first, on the host alone (a stand-in pointer takes the
     // workspace's place): a call that fails here has not touched the GPU.
-    const size_t need = tom_oqm_score_workspace_bytes(h, n_layers < 0 ? 0 : n_layers, t_q < 1 ? 1 : t_q,
-                                                      resolve_path(path, false), 0);
+    // (arguments the validation pass below refuses give 0 here, and are then refused there)
+    const size_t need = tom_oqm_score_workspace_bytes(h, n_layers, t_q, resolve_path(path, false), 0);
     if (need > kScratchBytes)
         return fail(TOM_ERR_UNSUPPORTED,
                     "the score step needs %zu bytes of scratch for %d layers and a %d-token query; the "

@@ -80,6 +80,8 @@ int main() {
     EXPECT(tom_oqm_quantize_append(h, 0, 2, 9, fake, fake, nullptr, st, 1, nullptr, &first), TOM_ERR_CAPACITY);
     EXPECT(tom_oqm_quantize_append(h, 1, 2, 1, fake, fake, nullptr, st, 1, nullptr, &first), TOM_ERR_INVALID_ARG);
     EXPECT(tom_oqm_quantize_append(h, 0, INT32_MAX, 1, fake, fake, nullptr, st, 1, nullptr, &first), TOM_ERR_INVALID_ARG);
+    EXPECT(tom_oqm_quantize_append(h, 1, INT32_MAX, 1, fake, fake, nullptr, st, 1, nullptr, &first), TOM_ERR_INVALID_ARG);
+    EXPECT(tom_oqm_dequant_gather(h, INT32_MAX, INT32_MAX, ifake, 4, 1, fake, fake, nullptr), TOM_ERR_INVALID_ARG);
     EXPECT(tom_oqm_quantize_append(h, 0, 2, -1, fake, fake, nullptr, st, 1, nullptr, &first), TOM_ERR_INVALID_ARG);
     EXPECT(tom_oqm_quantize_append(h, 0, 2, 1, nullptr, fake, nullptr, st, 1, nullptr, &first), TOM_ERR_INVALID_ARG);
     EXPECT(tom_oqm_quantize_append(h, 0, 2, 1, fake, fake, nullptr, nullptr, 1, nullptr, &first), TOM_ERR_INVALID_ARG);
@@ -102,8 +104,11 @@ int main() {
     EXPECT(tom_oqm_score_groups(h, 0, 2, fake, 9, 1, ffake, 8, nullptr, TOM_SCORE_AUTO, fake, 1 << 20, nullptr), TOM_ERR_INVALID_ARG);
     EXPECT(tom_oqm_score_groups(h, 0, 2, fake, TOM_F32, 0, ffake, 8, nullptr, TOM_SCORE_AUTO, fake, 1 << 20, nullptr), TOM_ERR_INVALID_ARG);
     EXPECT(tom_oqm_score_groups(h, 0, 2, fake, TOM_F32, 1, ffake, 8, ffake, TOM_SCORE_MEAN_QUERY, fake, 1 << 20, nullptr), TOM_ERR_INVALID_ARG);
-    EXPECT(tom_oqm_score_groups(h, 0, 2, fake, TOM_F32, INT32_MAX, ffake, 8, nullptr, TOM_SCORE_TOKEN_GEMM, fake, 1 << 20, nullptr), TOM_ERR_INVALID_ARG);
-    if (tom_oqm_score_workspace_bytes(h, 2, INT32_MAX, TOM_SCORE_TOKEN_GEMM, 0) < (size_t)INT32_MAX) ++failures;
+    EXPECT(tom_oqm_score_groups(h, 0, 2, fake, TOM_F32, INT32_MAX, ffake, 8, nullptr, TOM_SCORE_TOKEN_GEMM, fake, 1 << 20, nullptr), TOM_ERR_UNSUPPORTED);
+    EXPECT(tom_oqm_score_groups(h, 0, 2, fake, TOM_F32, 1 << 20, ffake, 8, nullptr, TOM_SCORE_TOKEN_GEMM, fake, 1 << 20, nullptr), TOM_ERR_INVALID_ARG);
+    if (tom_oqm_score_workspace_bytes(h, 2, INT32_MAX, TOM_SCORE_TOKEN_GEMM, 0) != 0) ++failures;
+    if (tom_oqm_score_workspace_bytes(h, INT32_MAX, 1, TOM_SCORE_TOKEN_GEMM, 0) != 0) ++failures;
+    if (tom_oqm_score_workspace_bytes(h, 2, 1 << 20, TOM_SCORE_TOKEN_GEMM, 0) < ((size_t)1 << 31)) ++failures;
     EXPECT(tom_oqm_topk(ffake, 16, 1, 10, 0, TOM_ORDER_INDEX_ASC, ifake, &k_eff, nullptr), TOM_ERR_INVALID_ARG);
     EXPECT(tom_oqm_topk(ffake, 5, 1, 10, 4, TOM_ORDER_INDEX_ASC, ifake, &k_eff, nullptr), TOM_ERR_INVALID_ARG);
     EXPECT(tom_oqm_topk(nullptr, 16, 1, 10, 4, TOM_ORDER_INDEX_ASC, ifake, &k_eff, nullptr), TOM_ERR_INVALID_ARG);
