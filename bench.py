@@ -92,6 +92,28 @@ def measured_traffic(kernel, workload):
     return None, f"{src} has no line for {kernel}"
 
 
+def traced_duration_us(kernel, workload):
+    """Average duration of `kernel` in the committed rocprofv3 kernel trace of
+    `bench.py --workload <workload>` (another run of the same kernel sources), or None."""
+    path = os.path.join(ROOT, "profiles", f"kernel_trace_bench_{workload.lower()}.txt")
+    try:
+        with open(path) as f:
+            lines = f.read().splitlines()
+    except OSError:
+        return None
+    stamped = [l.split()[1] for l in lines if l.startswith("kernel_sources_sha256 ") and len(l.split()) == 2]
+    if not stamped or stamped[0] != kernel_sources_hash():
+        return None
+    for line in lines:
+        if line.startswith(kernel + "<") or line.startswith(kernel + " "):
+            tail = line.rsplit(None, 5)      # name ... calls avg min max total
+            try:
+                return float(tail[2])
+            except (IndexError, ValueError):
+                return None
+    return None
+
+
 def load_probe_lib():
     """The benchmark-only shared object (stream probes); not part of the library."""
     path = os.path.join(ROOT, "paper_2510_18269_amd", "libtom_bench_probe.so")
@@ -341,11 +363,16 @@ class Leg:
 
         def roof(kernel, b, ms, probe):
             traffic, note = measured_traffic(kernel, w.name) if default_variant else (None, "not the default variant")
+            traced = traced_duration_us(kernel, w.name) if default_variant else None
             return {"bound": "hbm", "kernel": kernel, "achieved": round(gbps(b, ms), 1), "peak": HBM_PEAK_GBPS,
                     "unit": "GB/s", "frac": round(gbps(b, ms) / HBM_PEAK_GBPS, 4),
                     "frac_of_probe": round(gbps(b, ms) / probe, 4) if probe else None,
                     "traffic": traffic, "traffic_source": note,
-                    "algorithmic_bytes": b, "avg_launch_us": round(ms * 1e3, 2), "launches_timed": len(events)}
+                    "algorithmic_bytes": b, "avg_launch_us": round(ms * 1e3, 2), "launches_timed": len(events),
+                    # context: the same kernel in the committed rocprofv3 kernel trace (another run, same
+                    # sources); the event interval above is this plus the events' own cost
+                    "committed_kernel_trace_us": traced,
+                    "frac_by_committed_kernel_trace": round(b / (traced * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4) if traced else None}
 
         tok = self.tok
         r = {
